@@ -20,6 +20,8 @@ real activations / weights: X, dY ~ N(0,1), W, bias ~ N(0,0.02).
 from __future__ import annotations
 
 import dataclasses
+import os
+from concurrent.futures import ThreadPoolExecutor
 from typing import Dict, List, Optional, Tuple
 
 import numpy as np
@@ -30,6 +32,14 @@ _M64 = np.uint64(0xFFFFFFFFFFFFFFFF)
 STREAM_X, STREAM_W, STREAM_DY, STREAM_BIAS = 0, 1, 2, 3
 SIGMA_ACT = 1.0
 SIGMA_W = 0.02
+
+
+def _workers() -> int:
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    return max(1, min(16, n))
 
 
 def _splitmix64(x: np.ndarray) -> np.ndarray:
@@ -70,9 +80,10 @@ def normal_bf16_region(seed: int, stream: int, global_cols: int, row0: int, rows
         return out
     base = _stream_base(seed, stream)
     two_pi = 2.0 * np.pi
-    chunk = max(1, (1 << 22) // max(cols, 1))
+    chunk = max(1, (1 << 20) // max(cols, 1))
     cidx = np.arange(col0, col0 + cols, dtype=np.uint64)
-    for r in range(0, rows, chunk):
+
+    def fill(r: int) -> None:
         rr = np.arange(row0 + r, row0 + min(rows, r + chunk), dtype=np.uint64)
         idx = rr[:, None] * np.uint64(global_cols) + cidx[None, :]
         with np.errstate(over="ignore"):
@@ -83,6 +94,13 @@ def normal_bf16_region(seed: int, stream: int, global_cols: int, row0: int, rows
         u2 = (z2 >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)          # [0,1)
         g = np.sqrt(-2.0 * np.log(u1)) * np.cos(two_pi * u2) * sigma
         out[r:r + rr.shape[0]] = f32_to_bf16_bits(g.astype(np.float32))
+
+    starts = list(range(0, rows, chunk))
+    if len(starts) == 1:
+        fill(0)
+    else:  # numpy releases the GIL inside its loops; chunks are independent (counter based)
+        with ThreadPoolExecutor(max_workers=_workers()) as ex:
+            list(ex.map(fill, starts))
     return out
 
 

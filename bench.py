@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the shard-GEMM hot path on one MI355X.
+
+A step is one pass of the hot path over one workload: the forward, dgrad and wgrad local
+products of a 3D-tensor-parallel FC layer shard (for the chain workload: axo_layer_step over all
+layers).  Inputs are seeded synthetic bf16 shards, resident in HBM before the timed region.
+Prints one JSON line: TFLOP/s of the step (2*M*Kl*Nl flop per product), a roofline object for the
+slowest product's kernel (HIP-event timed on the launch stream) and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="cfg2", help="cfg1..cfg5 (default cfg2, the QKV shard)")
+    ap.add_argument("--all-configs", action="store_true", help="also time cfg2..cfg5 and report them under 'configs'")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU's share of the work on one GPU; "
+              "--gpus must be 1 (no collectives or multi-GPU path exist here).", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import axo_synth as syn
+    import paper_2305_13525_amd as axo
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    axo.library()  # fails loudly if the HIP library is not built
+    st = torch.cuda.current_stream().cuda_stream
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to("cuda:0")
+
+    def setup(cfg_name):
+        layers = syn.configs()[cfg_name]
+        objs, keep, flop = [], [], 0
+        for L in layers:
+            d = syn.layer_inputs(L)
+            p = axo.Problem.make(L.grid, (0, 0, 0), L.T, L.K, L.N)
+            M, Kl, Nl = L.shard
+            t = {k: dev(v) for k, v in d.items()}
+            t["Y"] = torch.zeros((M, Nl), dtype=torch.int16, device="cuda:0")
+            t["dX"] = torch.zeros((M, Kl), dtype=torch.int16, device="cuda:0")
+            t["dW"] = torch.zeros((Kl, Nl), dtype=torch.int16, device="cuda:0")
+            keep.append(t)
+            epi = L.epilogue
+            objs.append(axo.Layer(p, epi, 0, t["X"].data_ptr(), Kl, t["W"].data_ptr(), Nl,
+                                  t["bias"].data_ptr() if epi else None, t["Y"].data_ptr(), Nl,
+                                  t["dY"].data_ptr(), Nl, t["dX"].data_ptr(), Kl, t["dW"].data_ptr(), Nl))
+            flop += 3 * L.flop_per_gemm
+        nws = axo.axo_layer_step_workspace_bytes(objs)
+        ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda:0")
+        keep.append(ws)
+        return layers, objs, keep, flop, ws.data_ptr(), nws
+
+    def time_step(objs, wsp, nws, steps, warmup):
+        for _ in range(warmup):
+            axo.axo_layer_step(objs, wsp, nws, st)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            axo.axo_layer_step(objs, wsp, nws, st)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        return max(e0.elapsed_time(e1), 0.0) / steps, wall / steps
+
+    def time_op(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    def per_op(L, o, wsp, nws, steps, warmup):
+        res = {}
+        res["fwd"] = time_op(lambda: axo.axo_fc_fwd(o.p, o.X, o.ldx, o.W, o.ldw, o.bias, o.epilogue, o.Y, o.ldy,
+                                                    wsp, nws, st), steps, warmup)
+        res["dgrad"] = time_op(lambda: axo.axo_fc_dgrad(o.p, o.dY, o.lddy, o.W, o.ldw, o.dX, o.lddx, wsp, nws, st),
+                               steps, warmup)
+        res["wgrad"] = time_op(lambda: axo.axo_fc_wgrad(o.p, o.X, o.ldx, o.dY, o.lddy, o.dW, o.lddw, wsp, nws, st),
+                               steps, warmup)
+        return res
+
+    layers, objs, keep, flop, wsp, nws = setup(args.config)
+    ms, wall_ms = time_step(objs, wsp, nws, args.steps, args.warmup)
+    tflops = flop / (ms * 1e-3) / 1e12
+
+    # dominant kernel: the slowest of the products of the first (for cfg5: the largest) layer
+    li = max(range(len(layers)), key=lambda i: layers[i].flop_per_gemm)
+    ops = per_op(layers[li], objs[li], wsp, nws, args.steps, args.warmup)
+    dom = max(ops, key=ops.get)
+    gflop = layers[li].flop_per_gemm
+    ach = gflop / (ops[dom] * 1e-3) / 1e12
+    M, Kl, Nl = layers[li].shard
+    roofline = {"bound": "mfma", "kernel": f"{layers[li].name}.{dom}", "achieved": round(ach, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                "traffic": None, "flop_per_launch": gflop, "avg_launch_ms": round(ops[dom], 5),
+                "algorithmic_bytes_per_launch": 2 * (M * Kl + Kl * Nl + M * Nl),
+                "per_op_ms": {k: round(v, 5) for k, v in ops.items()},
+                "per_op_tflops": {k: round(gflop / (v * 1e-3) / 1e12, 2) for k, v in ops.items()}}
+
+    out = {"metric": "TFLOP/s for fwd+dgrad+wgrad shard GEMMs, 1 MI355X", "value": round(tflops, 2),
+           "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms, 5), "wall_ms_per_step": round(wall_ms, 5), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+           "config": {"workload": args.config, "layers": [
+               {"name": L.name, "grid": list(L.grid), "shard_MKN": list(L.shard), "epilogue": L.epilogue}
+               for L in layers], "flop_per_step": flop},
+           "roofline": roofline}
+
+    if args.all_configs:
+        extra = {}
+        for name in ("cfg2", "cfg3", "cfg4", "cfg5"):
+            if name == args.config:
+                extra[name] = {"tflops": round(tflops, 2), "ms_per_step": round(ms, 5)}
+                continue
+            del keep
+            torch.cuda.empty_cache()
+            l2, o2, keep, f2, w2, n2 = setup(name)
+            m2, _ = time_step(o2, w2, n2, args.steps, args.warmup)
+            extra[name] = {"tflops": round(f2 / (m2 * 1e-3) / 1e12, 2), "ms_per_step": round(m2, 5),
+                           "frac_of_peak": round(f2 / (m2 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+        out["configs"] = extra
+
+    if not args.no_cpu_baseline:
+        import oracle  # test infrastructure; only this baseline leg uses it
+        L = layers[li]
+        d = syn.layer_inputs(L)
+        M, Kl, Nl = L.shard
+        n_act = min(M, 768)
+        n_w = min(Kl, 384)
+        rows = np.linspace(0, M - 1, n_act).astype(np.int64)
+        krows = np.linspace(0, Kl - 1, n_w).astype(np.int64)
+        t0 = time.perf_counter()
+        oracle.fc_fwd(d["X"], d["W"], d["bias"] if L.epilogue else None, L.epilogue, rows=rows)
+        oracle.fc_dgrad(d["dY"], d["W"], rows=rows)
+        oracle.fc_wgrad(d["X"], d["dY"], rows=krows)
+        dt = time.perf_counter() - t0
+        cflop = 2.0 * (2 * n_act * Kl * Nl + n_w * M * Nl)
+        out["cpu_baseline"] = {"value": round(cflop / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "seconds": round(dt, 2),
+                               "sample": f"{L.name}: {n_act} of {M} output rows of fwd and of dgrad, "
+                                         f"{n_w} of {Kl} rows of dW (fp64 plain loops)"}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,164 @@
+/*
+ * axo.h -- C ABI of the MI355X (gfx950) shard-GEMM library for 3D tensor-parallel
+ * fully-connected layers.
+ *
+ * The operation (paper Section 3.2, "Three-dimensional Tensor Parallelism"; Figure 1;
+ * Algorithm 1): an FC layer O = I x W with I in R^{m x k}, W in R^{k x n} is spread over a
+ * virtual Gx x Gy x Gz grid of GPUs.  GPU g_{ix,iy,iz} holds one 2D block of I and one of W
+ * and computes three local matrix products per layer:
+ *
+ *   forward  (Algorithm 1, forward function, local multiply)     Y_part  = X  . W
+ *   dgrad    (Algorithm 1, backward function, first product)     dX_part = dY . W^T
+ *   wgrad    (Algorithm 1, backward function, second product)    dW_part = X^T . dY
+ *
+ * The collectives that combine the partial results across GPUs are not part of this library;
+ * it reproduces exactly one GPU's share of the work.
+ *
+ * Naming: T = m (tokens of one tensor-parallel group), K = k (in-features), N = n
+ * (out-features), X = I, Y = O, dY = dL/dO, dX = dL/dI, dW = dL/dW.
+ * Axis mapping: with transposed == 0 the reduction dimension K is split over Gx, N over Gy and
+ * T over Gz; with transposed == 1 the roles of the X and Y axes are swapped (K over Gy, N over
+ * Gx), which is the mapping of Algorithm 1 as printed and, per Section 3.2 ("Parallelizing an
+ * entire network"), the one every second layer uses.  Local shard sizes are
+ * M = T/Gz, Kl = K/G(k-axis), Nl = N/G(n-axis).
+ *
+ * Data: every matrix is row-major bf16 (bit patterns, 2 bytes per element) in DEVICE memory,
+ * W stored [Kl x Nl] as the paper writes it.  Products accumulate in fp32 and are rounded once,
+ * round-to-nearest-even, to bf16 at the store.  Leading dimensions are in elements and allow a
+ * shard to be addressed in place inside a larger matrix.
+ *
+ * Ownership: the caller owns all buffers; the library allocates nothing, keeps no pointer after
+ * a call returns, and only enqueues work on the caller's HIP stream (no device synchronisation,
+ * no host read-back).  Buffers must stay valid until the stream has executed the call.
+ * Outputs must not alias inputs.  A matrix with no elements (a zero shard dimension) is never
+ * dereferenced: its pointer may be NULL and its leading dimension is not checked.
+ *
+ * Errors: every function returns an int status, 0 on success, negative on error; nothing throws
+ * or aborts.  All argument checks happen on the host before the first HIP call, so every status
+ * except AXO_ERR_HIP can be produced without a GPU.
+ */
+#ifndef AXO_H
+#define AXO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AXO_VERSION 1
+
+typedef enum axo_status {
+    AXO_OK = 0,
+    AXO_ERR_BAD_GRID = -1,     /* a grid dimension < 1                                           */
+    AXO_ERR_BAD_COORD = -2,    /* coordinate outside the grid                                    */
+    AXO_ERR_INDIVISIBLE = -3,  /* T, K or N not divisible by its grid dimension                  */
+    AXO_ERR_NULL_PTR = -4,     /* a required pointer is NULL                                     */
+    AXO_ERR_MISALIGNED = -5,   /* pointer not 16-byte aligned, or leading dimension not a        */
+                               /* multiple of 8 elements                                         */
+    AXO_ERR_BAD_LD = -6,       /* leading dimension smaller than the row length                  */
+    AXO_ERR_WORKSPACE = -7,    /* workspace smaller than axo_workspace_bytes() asks for          */
+    AXO_ERR_BAD_EPILOGUE = -8, /* unknown epilogue, or an epilogue with bias == NULL             */
+    AXO_ERR_HIP = -9,          /* a HIP launch failed (the only status that needs a device)      */
+    AXO_ERR_BAD_SIZE = -10,    /* T, K or N < 0, or a shard dimension beyond 2^31-1              */
+    AXO_ERR_BAD_ARG = -11      /* anything else malformed (unknown op, n_layers < 0, ...)        */
+} axo_status_t;
+
+/* The problem statement of Section 3.2: grid, this GPU's coordinate, global sizes. */
+typedef struct axo_problem {
+    int32_t Gx, Gy, Gz; /* grid dimensions, each >= 1                                   */
+    int32_t ix, iy, iz; /* this GPU is g_{ix,iy,iz}: 0 <= ix < Gx, and so on            */
+    int64_t T, K, N;    /* GLOBAL tokens, in-features, out-features (each >= 0)         */
+    int32_t transposed; /* 0: K over Gx, N over Gy.  1: K over Gy, N over Gx            */
+    int32_t reserved;   /* must be 0                                                    */
+} axo_problem_t;
+
+/* Epilogue of the forward product.  Not part of the paper: the usual GPT MLP epilogue, fused
+ * on the fp32 accumulator before the one rounding to bf16.
+ * The bias vector is added only on shards whose coordinate along the axis that splits K is 0,
+ * so that summing the partial products of that axis adds it exactly once.  The activation is
+ * applied to this shard's (partial + bias); that equals the layer's activation only when the
+ * K-splitting axis has size 1 (otherwise it is a kernel-shape measurement, since the true
+ * activation must follow the all-reduce of Algorithm 1's forward function). */
+typedef enum axo_epilogue {
+    AXO_EPI_NONE = 0,
+    AXO_EPI_BIAS = 1,           /* y + b                                                          */
+    AXO_EPI_BIAS_GELU_TANH = 2, /* v = y + b;  0.5 v (1 + tanh( sqrt(2/pi) (v + 0.044715 v^3) ))  */
+    AXO_EPI_BIAS_GELU_ERF = 3   /* v = y + b;  0.5 v (1 + erf( v / sqrt(2) ))                     */
+} axo_epilogue_t;
+
+typedef enum axo_op { AXO_OP_FWD = 0, AXO_OP_DGRAD = 1, AXO_OP_WGRAD = 2 } axo_op_t;
+
+/* Library version (AXO_VERSION of the build). */
+int axo_version(void);
+
+/* Static, never NULL, human-readable text for a status code. */
+const char *axo_status_string(int status);
+
+/* Host only.  Validates the problem and derives this GPU's shard: local sizes M, Kl, Nl and the
+ * offsets of its blocks in the global matrices (X block at [row0, k0], W block at [k0, n0],
+ * Y / dY block at [row0, n0]).  Any output pointer may be NULL.
+ * Errors: NULL_PTR (p), BAD_GRID, BAD_COORD, BAD_SIZE, INDIVISIBLE, BAD_ARG (reserved != 0 or
+ * transposed not 0/1). */
+int axo_shard_dims(const axo_problem_t *p, int64_t *M, int64_t *Kl, int64_t *Nl,
+                   int64_t *row0, int64_t *k0, int64_t *n0);
+
+/* Host only.  Bytes of device workspace the given op (axo_op_t) of this problem needs; 0 when
+ * none.  The workspace holds fp32 partial sums when the reduction dimension is split inside one
+ * GPU; it need not be initialised and may be reused by the next call on the same stream.
+ * Returns 0 for an invalid problem (the op call itself reports the error). */
+size_t axo_workspace_bytes(const axo_problem_t *p, int op);
+
+/* Forward local product  Y[M x Nl] = epilogue( X[M x Kl] . W[Kl x Nl] ).
+ * X, W, Y: device pointers, bf16, row-major, 16-byte aligned; ldx >= Kl, ldw >= Nl, ldy >= Nl,
+ * each a multiple of 8.  bias: device pointer to Nl bf16 values (16-byte aligned) or NULL when
+ * epilogue == AXO_EPI_NONE.  ws / ws_bytes: device workspace of at least
+ * axo_workspace_bytes(p, AXO_OP_FWD) bytes (may be NULL when that is 0).  hip_stream: a
+ * hipStream_t (NULL = the default stream).  A shard with M, Kl or Nl == 0 is valid: with
+ * Kl == 0 the output is epilogue(0); with M or Nl == 0 nothing is written. */
+int axo_fc_fwd(const axo_problem_t *p, const void *X, int64_t ldx, const void *W, int64_t ldw,
+               const void *bias, int epilogue, void *Y, int64_t ldy,
+               void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Backward data gradient  dX[M x Kl] = dY[M x Nl] . W[Kl x Nl]^T.
+ * lddy >= Nl, ldw >= Nl, lddx >= Kl; same alignment rules; workspace per AXO_OP_DGRAD. */
+int axo_fc_dgrad(const axo_problem_t *p, const void *dY, int64_t lddy, const void *W, int64_t ldw,
+                 void *dX, int64_t lddx, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Backward weight gradient  dW[Kl x Nl] = X[M x Kl]^T . dY[M x Nl].
+ * ldx >= Kl, lddy >= Nl, lddw >= Nl; same alignment rules; workspace per AXO_OP_WGRAD. */
+int axo_fc_wgrad(const axo_problem_t *p, const void *X, int64_t ldx, const void *dY, int64_t lddy,
+                 void *dW, int64_t lddw, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* One FC layer of a chain: its problem, epilogue, and the caller's buffers with their leading
+ * dimensions.  X and W are kept by the caller between forward and backward (the cache of
+ * Algorithm 1's forward function).  dY is the gradient with respect to the layer's output
+ * before the activation. */
+typedef struct axo_layer {
+    axo_problem_t p;
+    int32_t epilogue; /* axo_epilogue_t */
+    int32_t reserved; /* must be 0      */
+    const void *X;    int64_t ldx;
+    const void *W;    int64_t ldw;
+    const void *bias;           /* NULL unless epilogue != AXO_EPI_NONE */
+    void *Y;          int64_t ldy;
+    const void *dY;   int64_t lddy;
+    void *dX;         int64_t lddx;
+    void *dW;         int64_t lddw;
+} axo_layer_t;
+
+/* Host only.  Largest workspace any single product of the chain needs. */
+size_t axo_layer_step_workspace_bytes(const axo_layer_t *layers, int n_layers);
+
+/* Forward of layers 0..n-1, then for layers n-1..0 the backward pair in the order dgrad, wgrad
+ * (Section 4.1 issues the dgrad all-reduce before computing wgrad, which fixes this order), all
+ * enqueued on one stream without host synchronisation.  All layers are validated before the
+ * first launch; on a validation error nothing is enqueued. */
+int axo_layer_step(const axo_layer_t *layers, int n_layers, void *ws, size_t ws_bytes,
+                   void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AXO_H */

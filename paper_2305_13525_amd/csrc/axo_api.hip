@@ -1,0 +1,255 @@
+// C ABI of the shard-GEMM library: host-side validation, shard derivation, kernel selection and
+// launch.  Every check runs before the first HIP call, so all statuses except AXO_ERR_HIP can be
+// exercised on a machine without a GPU.
+#include "../../include/axo.h"
+
+#include <hip/hip_runtime.h>
+
+#include <new>
+
+#include "axo_common.hpp"
+#include "gemm_generic.hpp"
+
+namespace {
+
+using axo::GemmArgs;
+
+struct Shard {
+    int64_t M, Kl, Nl, row0, k0, n0;
+    int k_coord;  // coordinate along the axis that splits K
+};
+
+int derive_shard(const axo_problem_t* p, Shard* s) {
+    if (!p) return AXO_ERR_NULL_PTR;
+    if (p->reserved != 0 || (p->transposed != 0 && p->transposed != 1)) return AXO_ERR_BAD_ARG;
+    if (p->Gx < 1 || p->Gy < 1 || p->Gz < 1) return AXO_ERR_BAD_GRID;
+    if (p->ix < 0 || p->ix >= p->Gx || p->iy < 0 || p->iy >= p->Gy || p->iz < 0 || p->iz >= p->Gz)
+        return AXO_ERR_BAD_COORD;
+    if (p->T < 0 || p->K < 0 || p->N < 0) return AXO_ERR_BAD_SIZE;
+    // Section 3.2: I is cut over the token axis (Z) and the reduction axis, W over the reduction
+    // axis and the output axis.  transposed swaps which of X / Y plays which role.
+    const int gk = p->transposed ? p->Gy : p->Gx, ik = p->transposed ? p->iy : p->ix;
+    const int gn = p->transposed ? p->Gx : p->Gy, in = p->transposed ? p->ix : p->iy;
+    if (p->T % p->Gz != 0 || p->K % gk != 0 || p->N % gn != 0) return AXO_ERR_INDIVISIBLE;
+    s->M = p->T / p->Gz;
+    s->Kl = p->K / gk;
+    s->Nl = p->N / gn;
+    if (s->M > INT32_MAX || s->Kl > INT32_MAX || s->Nl > INT32_MAX) return AXO_ERR_BAD_SIZE;
+    s->row0 = s->M * p->iz;
+    s->k0 = s->Kl * ik;
+    s->n0 = s->Nl * in;
+    s->k_coord = ik;
+    return AXO_OK;
+}
+
+bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+// One matrix argument: pointer, leading dimension, row length.  A matrix without elements is
+// never dereferenced, so nothing about it is checked.
+int check_matrix(const void* ptr, int64_t ld, int64_t rows, int64_t row_len) {
+    if (rows == 0 || row_len == 0) return AXO_OK;
+    if (!ptr) return AXO_ERR_NULL_PTR;
+    if (ld < row_len) return AXO_ERR_BAD_LD;
+    if (!aligned16(ptr) || (ld % 8) != 0) return AXO_ERR_MISALIGNED;
+    return AXO_OK;
+}
+
+int launch(const GemmArgs& g, int la, int lb, hipStream_t st) {
+    if (g.Mo == 0 || g.No == 0) return AXO_OK;
+    dim3 grid((g.No + axo::GEN_BN - 1) / axo::GEN_BN, (g.Mo + axo::GEN_BM - 1) / axo::GEN_BM, 1);
+    dim3 block(256, 1, 1);
+    if (grid.y > 65535u) return AXO_ERR_BAD_SIZE;
+    if (la == axo::KC && lb == axo::MC)
+        hipLaunchKernelGGL((axo::gemm_generic_kernel<axo::KC, axo::MC>), grid, block, 0, st, g);
+    else if (la == axo::KC && lb == axo::KC)
+        hipLaunchKernelGGL((axo::gemm_generic_kernel<axo::KC, axo::KC>), grid, block, 0, st, g);
+    else
+        hipLaunchKernelGGL((axo::gemm_generic_kernel<axo::MC, axo::MC>), grid, block, 0, st, g);
+    return hipGetLastError() == hipSuccess ? AXO_OK : AXO_ERR_HIP;
+}
+
+// Validated, launch-ready description of one product.
+struct Plan {
+    GemmArgs g;
+    int la, lb;
+};
+
+int plan_fwd(const axo_problem_t* p, const void* X, int64_t ldx, const void* W, int64_t ldw, const void* bias,
+             int epilogue, void* Y, int64_t ldy, void* ws, size_t ws_bytes, Plan* out) {
+    Shard s;
+    int rc = derive_shard(p, &s);
+    if (rc) return rc;
+    if (epilogue < AXO_EPI_NONE || epilogue > AXO_EPI_BIAS_GELU_ERF) return AXO_ERR_BAD_EPILOGUE;
+    if (epilogue != AXO_EPI_NONE && !bias) return AXO_ERR_BAD_EPILOGUE;
+    if ((rc = check_matrix(X, ldx, s.M, s.Kl))) return rc;
+    if ((rc = check_matrix(W, ldw, s.Kl, s.Nl))) return rc;
+    if ((rc = check_matrix(Y, ldy, s.M, s.Nl))) return rc;
+    if (epilogue != AXO_EPI_NONE && !aligned16(bias)) return AXO_ERR_MISALIGNED;
+    if (ws_bytes < axo_workspace_bytes(p, AXO_OP_FWD) || (axo_workspace_bytes(p, AXO_OP_FWD) && !ws))
+        return AXO_ERR_WORKSPACE;
+    GemmArgs& g = out->g;
+    g.A = static_cast<const axo::bf16_t*>(X); g.lda = ldx;
+    g.B = static_cast<const axo::bf16_t*>(W); g.ldb = ldw;
+    g.C = static_cast<axo::bf16_t*>(Y); g.ldc = ldy;
+    g.bias = static_cast<const axo::bf16_t*>(bias);
+    g.Mo = (int)s.M; g.No = (int)s.Nl; g.R = (int)s.Kl;
+    g.epilogue = epilogue;
+    g.add_bias = (epilogue != AXO_EPI_NONE && s.k_coord == 0) ? 1 : 0;
+    g.ws = static_cast<float*>(ws); g.splits = 1;
+    out->la = axo::KC; out->lb = axo::MC;
+    return AXO_OK;
+}
+
+int plan_dgrad(const axo_problem_t* p, const void* dY, int64_t lddy, const void* W, int64_t ldw, void* dX,
+               int64_t lddx, void* ws, size_t ws_bytes, Plan* out) {
+    Shard s;
+    int rc = derive_shard(p, &s);
+    if (rc) return rc;
+    if ((rc = check_matrix(dY, lddy, s.M, s.Nl))) return rc;
+    if ((rc = check_matrix(W, ldw, s.Kl, s.Nl))) return rc;
+    if ((rc = check_matrix(dX, lddx, s.M, s.Kl))) return rc;
+    if (ws_bytes < axo_workspace_bytes(p, AXO_OP_DGRAD) || (axo_workspace_bytes(p, AXO_OP_DGRAD) && !ws))
+        return AXO_ERR_WORKSPACE;
+    GemmArgs& g = out->g;
+    g.A = static_cast<const axo::bf16_t*>(dY); g.lda = lddy;
+    g.B = static_cast<const axo::bf16_t*>(W); g.ldb = ldw;
+    g.C = static_cast<axo::bf16_t*>(dX); g.ldc = lddx;
+    g.bias = nullptr;
+    g.Mo = (int)s.M; g.No = (int)s.Kl; g.R = (int)s.Nl;
+    g.epilogue = AXO_EPI_NONE; g.add_bias = 0;
+    g.ws = static_cast<float*>(ws); g.splits = 1;
+    out->la = axo::KC; out->lb = axo::KC;
+    return AXO_OK;
+}
+
+int plan_wgrad(const axo_problem_t* p, const void* X, int64_t ldx, const void* dY, int64_t lddy, void* dW,
+               int64_t lddw, void* ws, size_t ws_bytes, Plan* out) {
+    Shard s;
+    int rc = derive_shard(p, &s);
+    if (rc) return rc;
+    if ((rc = check_matrix(X, ldx, s.M, s.Kl))) return rc;
+    if ((rc = check_matrix(dY, lddy, s.M, s.Nl))) return rc;
+    if ((rc = check_matrix(dW, lddw, s.Kl, s.Nl))) return rc;
+    if (ws_bytes < axo_workspace_bytes(p, AXO_OP_WGRAD) || (axo_workspace_bytes(p, AXO_OP_WGRAD) && !ws))
+        return AXO_ERR_WORKSPACE;
+    GemmArgs& g = out->g;
+    g.A = static_cast<const axo::bf16_t*>(X); g.lda = ldx;
+    g.B = static_cast<const axo::bf16_t*>(dY); g.ldb = lddy;
+    g.C = static_cast<axo::bf16_t*>(dW); g.ldc = lddw;
+    g.bias = nullptr;
+    g.Mo = (int)s.Kl; g.No = (int)s.Nl; g.R = (int)s.M;
+    g.epilogue = AXO_EPI_NONE; g.add_bias = 0;
+    g.ws = static_cast<float*>(ws); g.splits = 1;
+    out->la = axo::MC; out->lb = axo::MC;
+    return AXO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int axo_version(void) { return AXO_VERSION; }
+
+const char* axo_status_string(int status) {
+    switch (status) {
+        case AXO_OK: return "ok";
+        case AXO_ERR_BAD_GRID: return "grid dimension < 1";
+        case AXO_ERR_BAD_COORD: return "grid coordinate outside the grid";
+        case AXO_ERR_INDIVISIBLE: return "T, K or N not divisible by its grid dimension";
+        case AXO_ERR_NULL_PTR: return "required pointer is NULL";
+        case AXO_ERR_MISALIGNED: return "pointer not 16-byte aligned or leading dimension not a multiple of 8";
+        case AXO_ERR_BAD_LD: return "leading dimension smaller than the row length";
+        case AXO_ERR_WORKSPACE: return "workspace too small";
+        case AXO_ERR_BAD_EPILOGUE: return "unknown epilogue or epilogue without bias";
+        case AXO_ERR_HIP: return "HIP launch failed";
+        case AXO_ERR_BAD_SIZE: return "negative size or shard dimension beyond 2^31-1";
+        case AXO_ERR_BAD_ARG: return "malformed argument";
+        default: return "unknown status";
+    }
+}
+
+int axo_shard_dims(const axo_problem_t* p, int64_t* M, int64_t* Kl, int64_t* Nl, int64_t* row0, int64_t* k0,
+                   int64_t* n0) {
+    Shard s;
+    int rc = derive_shard(p, &s);
+    if (rc) return rc;
+    if (M) *M = s.M;
+    if (Kl) *Kl = s.Kl;
+    if (Nl) *Nl = s.Nl;
+    if (row0) *row0 = s.row0;
+    if (k0) *k0 = s.k0;
+    if (n0) *n0 = s.n0;
+    return AXO_OK;
+}
+
+size_t axo_workspace_bytes(const axo_problem_t* p, int op) {
+    Shard s;
+    if (derive_shard(p, &s) != AXO_OK) return 0;
+    if (op < AXO_OP_FWD || op > AXO_OP_WGRAD) return 0;
+    return 0;
+}
+
+int axo_fc_fwd(const axo_problem_t* p, const void* X, int64_t ldx, const void* W, int64_t ldw, const void* bias,
+               int epilogue, void* Y, int64_t ldy, void* ws, size_t ws_bytes, void* hip_stream) {
+    Plan pl;
+    int rc = plan_fwd(p, X, ldx, W, ldw, bias, epilogue, Y, ldy, ws, ws_bytes, &pl);
+    if (rc) return rc;
+    return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+}
+
+int axo_fc_dgrad(const axo_problem_t* p, const void* dY, int64_t lddy, const void* W, int64_t ldw, void* dX,
+                 int64_t lddx, void* ws, size_t ws_bytes, void* hip_stream) {
+    Plan pl;
+    int rc = plan_dgrad(p, dY, lddy, W, ldw, dX, lddx, ws, ws_bytes, &pl);
+    if (rc) return rc;
+    return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+}
+
+int axo_fc_wgrad(const axo_problem_t* p, const void* X, int64_t ldx, const void* dY, int64_t lddy, void* dW,
+                 int64_t lddw, void* ws, size_t ws_bytes, void* hip_stream) {
+    Plan pl;
+    int rc = plan_wgrad(p, X, ldx, dY, lddy, dW, lddw, ws, ws_bytes, &pl);
+    if (rc) return rc;
+    return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t axo_layer_step_workspace_bytes(const axo_layer_t* layers, int n_layers) {
+    size_t need = 0;
+    if (!layers) return 0;
+    for (int i = 0; i < n_layers; ++i)
+        for (int op = AXO_OP_FWD; op <= AXO_OP_WGRAD; ++op) {
+            size_t b = axo_workspace_bytes(&layers[i].p, op);
+            if (b > need) need = b;
+        }
+    return need;
+}
+
+int axo_layer_step(const axo_layer_t* layers, int n_layers, void* ws, size_t ws_bytes, void* hip_stream) {
+    if (n_layers < 0) return AXO_ERR_BAD_ARG;
+    if (n_layers == 0) return AXO_OK;
+    if (!layers) return AXO_ERR_NULL_PTR;
+    if (n_layers > 4096) return AXO_ERR_BAD_ARG;
+    // validate the whole chain first: nothing is enqueued unless every product is well formed
+    Plan* plans = new (std::nothrow) Plan[3 * (size_t)n_layers];
+    if (!plans) return AXO_ERR_BAD_ARG;
+    int rc = AXO_OK;
+    for (int i = 0; i < n_layers && rc == AXO_OK; ++i) {
+        const axo_layer_t& L = layers[i];
+        if (L.reserved != 0) { rc = AXO_ERR_BAD_ARG; break; }
+        rc = plan_fwd(&L.p, L.X, L.ldx, L.W, L.ldw, L.bias, L.epilogue, L.Y, L.ldy, ws, ws_bytes, &plans[3 * i]);
+        if (rc) break;
+        rc = plan_dgrad(&L.p, L.dY, L.lddy, L.W, L.ldw, L.dX, L.lddx, ws, ws_bytes, &plans[3 * i + 1]);
+        if (rc) break;
+        rc = plan_wgrad(&L.p, L.X, L.ldx, L.dY, L.lddy, L.dW, L.lddw, ws, ws_bytes, &plans[3 * i + 2]);
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    for (int i = 0; i < n_layers && rc == AXO_OK; ++i) rc = launch(plans[3 * i].g, plans[3 * i].la, plans[3 * i].lb, st);
+    for (int i = n_layers - 1; i >= 0 && rc == AXO_OK; --i) {
+        rc = launch(plans[3 * i + 1].g, plans[3 * i + 1].la, plans[3 * i + 1].lb, st);
+        if (rc == AXO_OK) rc = launch(plans[3 * i + 2].g, plans[3 * i + 2].la, plans[3 * i + 2].lb, st);
+    }
+    delete[] plans;
+    return rc;
+}
+
+}  // extern "C"

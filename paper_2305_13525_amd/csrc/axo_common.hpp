@@ -1,0 +1,71 @@
+// Shared device helpers for the gfx950 shard-GEMM kernels: vector types, bf16 conversion,
+// epilogue math.  Wave size is 64 everywhere.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace axo {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+typedef uint16_t bf16_t;  // bf16 bit pattern in memory
+
+// Operand layouts of C[i,j] = sum_r A(i,r) * B(j,r):
+//   KC: the reduction index r is contiguous in memory   (element (i,r) at i*ld + r)
+//   MC: the output index i (or j) is contiguous         (element (i,r) at r*ld + i)
+enum Layout { KC = 0, MC = 1 };
+
+enum Epilogue { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_GELU_TANH = 2, EPI_BIAS_GELU_ERF = 3 };
+
+// One GEMM as the kernels see it.
+struct GemmArgs {
+    const bf16_t* A; int64_t lda;
+    const bf16_t* B; int64_t ldb;
+    bf16_t* C;       int64_t ldc;
+    const bf16_t* bias;  // [No] or nullptr
+    int Mo, No, R;       // output rows, output cols, reduction length
+    int epilogue;        // Epilogue
+    int add_bias;        // 0: bias pointer ignored (shard is not at K-coordinate 0)
+    float* ws;           // fp32 partial sums for split reductions (or nullptr)
+    int splits;          // number of reduction splits (1 = none)
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(bf16_t b) {
+    return __uint_as_float(((uint32_t)b) << 16);
+}
+
+// fp32 -> bf16 bits, round to nearest, ties to even; NaN stays NaN (quiet).
+__device__ __forceinline__ bf16_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// GELU, tanh form: 0.5 v (1 + tanh(z)) = v * sigmoid(2 z), z = sqrt(2/pi) (v + 0.044715 v^3).
+// The sigmoid form has no cancellation for large negative v.
+__device__ __forceinline__ float gelu_tanh(float v) {
+    const float c = 0.7978845608028654f;
+    float z = c * (v + 0.044715f * v * v * v);
+    return v / (1.0f + __expf(-2.0f * z));
+}
+
+// GELU, erf form: 0.5 v (1 + erf(v / sqrt 2)) = 0.5 v erfc(-v / sqrt 2)  (no cancellation).
+__device__ __forceinline__ float gelu_erf(float v) {
+    return 0.5f * v * erfcf(-v * 0.7071067811865475f);
+}
+
+__device__ __forceinline__ float apply_epilogue(float acc, float b, int epi) {
+    float v = acc + b;
+    if (epi == EPI_BIAS_GELU_TANH) v = gelu_tanh(v);
+    else if (epi == EPI_BIAS_GELU_ERF) v = gelu_erf(v);
+    return v;
+}
+
+}  // namespace axo

@@ -1,0 +1,163 @@
+"""Host-side tests of the C ABI (no GPU): the library loads, exports every function that
+include/axo.h declares, derives shards the way Section 3.2 of the paper cuts I and W over the
+grid, and turns every malformed argument into its status code before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+import paper_2305_13525_amd as axo
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "axo.h")
+
+OK, BAD_GRID, BAD_COORD, INDIVISIBLE, NULL_PTR, MISALIGNED, BAD_LD, WORKSPACE, BAD_EPI, HIP, BAD_SIZE, BAD_ARG = (
+    0, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10, -11)
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(axo_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"axo_fc_fwd", "axo_fc_dgrad", "axo_fc_wgrad", "axo_layer_step", "axo_shard_dims",
+            "axo_workspace_bytes", "axo_status_string", "axo_version",
+            "axo_layer_step_workspace_bytes"} <= set(names)
+    lib = ctypes.CDLL(axo.library_path())
+    for n in names:
+        assert hasattr(lib, n), n
+    assert axo.axo_version() == 1
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(axo.Problem) == 56
+    assert axo.Problem.T.offset == 24 and axo.Problem.transposed.offset == 48
+    assert ctypes.sizeof(axo.Layer) == 56 + 8 + 13 * 8
+    assert axo.Layer.X.offset == 64 and axo.Layer.bias.offset == 96 and axo.Layer.dW.offset == 152
+
+
+def test_status_strings():
+    seen = set()
+    for s in range(0, -12, -1):
+        t = axo.axo_status_string(s)
+        assert t and t != "unknown status" and t not in seen
+        seen.add(t)
+    assert axo.axo_status_string(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("transposed", [0, 1])
+def test_shard_dims_match_oracle_slices(transposed):
+    T, K, N, grid = 48, 72, 120, (2, 3, 4)
+    for ix in range(2):
+        for iy in range(3):
+            for iz in range(4):
+                p = axo.Problem.make(grid, (ix, iy, iz), T, K, N, transposed)
+                rc, (M, Kl, Nl, row0, k0, n0) = axo.axo_shard_dims(p)
+                rt, rk, rn = oracle.shard_slices(T, K, N, grid, (ix, iy, iz), bool(transposed))
+                assert (row0, row0 + M) == (rt.start, rt.stop)
+                assert (k0, k0 + Kl) == (rk.start, rk.stop)
+                assert (n0, n0 + Nl) == (rn.start, rn.stop)
+
+
+def test_benchmark_shard_shapes():
+    want = {((2, 2, 4), 16384, 4096, 12288): (4096, 2048, 6144),
+            ((4, 2, 8), 32768, 8192, 32768): (4096, 2048, 16384),
+            ((2, 4, 8), 32768, 32768, 8192): (4096, 16384, 2048),
+            ((8, 8, 4), 16384, 12288, 36864): (4096, 1536, 4608),
+            ((8, 8, 4), 16384, 49152, 12288): (4096, 6144, 1536)}
+    for (grid, T, K, N), shard in want.items():
+        rc, d = axo.axo_shard_dims(axo.Problem.make(grid, (0, 0, 0), T, K, N))
+        assert d[:3] == shard
+
+
+def test_shard_dims_errors():
+    mk = axo.Problem.make
+    sd = lambda p: axo.axo_shard_dims(p, check=False)[0]
+    assert sd(None) == NULL_PTR
+    assert sd(mk((0, 1, 1), (0, 0, 0), 8, 8, 8)) == BAD_GRID
+    assert sd(mk((1, -2, 1), (0, 0, 0), 8, 8, 8)) == BAD_GRID
+    assert sd(mk((2, 2, 2), (2, 0, 0), 8, 8, 8)) == BAD_COORD
+    assert sd(mk((2, 2, 2), (0, 0, -1), 8, 8, 8)) == BAD_COORD
+    assert sd(mk((2, 2, 2), (0, 0, 0), 9, 8, 8)) == INDIVISIBLE
+    assert sd(mk((2, 2, 2), (0, 0, 0), 8, 9, 8)) == INDIVISIBLE
+    assert sd(mk((2, 4, 2), (0, 0, 0), 8, 8, 10)) == INDIVISIBLE
+    assert sd(mk((2, 4, 2), (0, 0, 0), 8, 10, 8, 1)) == INDIVISIBLE   # transposed: K over Gy
+    assert sd(mk((2, 4, 2), (0, 0, 0), 8, 8, 10, 1)) == OK            # transposed: N over Gx
+    assert sd(mk((1, 1, 1), (0, 0, 0), -1, 8, 8)) == BAD_SIZE
+    assert sd(mk((1, 1, 1), (0, 0, 0), 2 ** 33, 8, 8)) == BAD_SIZE
+    assert sd(mk((1, 1, 1), (0, 0, 0), 8, 8, 8, 2)) == BAD_ARG
+    bad = mk((1, 1, 1), (0, 0, 0), 8, 8, 8)
+    bad.reserved = 7
+    assert sd(bad) == BAD_ARG
+    with pytest.raises(axo.AxoError):
+        axo.axo_shard_dims(mk((0, 1, 1), (0, 0, 0), 8, 8, 8))
+
+
+# The pointer checks below never reach a HIP call: every call is malformed on purpose, so the
+# fake addresses are never dereferenced.
+A = 0x10000  # 16-byte aligned fake device address
+
+
+def test_fwd_argument_errors():
+    p = axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 48)
+    f = lambda **kw: axo.axo_fc_fwd(**{**dict(p=p, X=A, ldx=32, W=A, ldw=48, bias=None, epilogue=0, Y=A, ldy=48,
+                                            check=False), **kw})
+    assert f(p=None) == NULL_PTR
+    assert f(X=None) == NULL_PTR and f(W=None) == NULL_PTR and f(Y=None) == NULL_PTR
+    assert f(ldx=24) == BAD_LD and f(ldw=40) == BAD_LD and f(ldy=8) == BAD_LD
+    assert f(ldx=36) == MISALIGNED and f(X=A + 2) == MISALIGNED and f(Y=A + 8) == MISALIGNED
+    assert f(epilogue=4) == BAD_EPI and f(epilogue=-1) == BAD_EPI
+    assert f(epilogue=1, bias=None) == BAD_EPI
+    assert f(epilogue=2, bias=A + 2) == MISALIGNED
+    assert f(p=axo.Problem.make((2, 1, 1), (0, 0, 0), 64, 33, 48)) == INDIVISIBLE
+
+
+def test_dgrad_wgrad_argument_errors():
+    p = axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 48)
+    d = lambda **kw: axo.axo_fc_dgrad(**{**dict(p=p, dY=A, lddy=48, W=A, ldw=48, dX=A, lddx=32, check=False), **kw})
+    w = lambda **kw: axo.axo_fc_wgrad(**{**dict(p=p, X=A, ldx=32, dY=A, lddy=48, dW=A, lddw=48, check=False), **kw})
+    assert d(dY=None) == NULL_PTR and d(W=None) == NULL_PTR and d(dX=None) == NULL_PTR
+    assert d(lddy=40) == BAD_LD and d(lddx=24) == BAD_LD and d(ldw=50) == MISALIGNED
+    assert w(X=None) == NULL_PTR and w(dY=None) == NULL_PTR and w(dW=None) == NULL_PTR
+    assert w(ldx=16) == BAD_LD and w(lddw=40) == BAD_LD and w(dW=A + 4) == MISALIGNED
+    assert d(p=None) == NULL_PTR and w(p=None) == NULL_PTR
+
+
+def test_empty_shards_need_no_device():
+    # M == 0 or Nl == 0: valid, nothing is launched, so this runs without a GPU
+    p0 = axo.Problem.make((1, 1, 1), (0, 0, 0), 0, 32, 48)
+    assert axo.axo_fc_fwd(p0, A, 32, A, 48, None, 0, A, 48, check=False) == OK
+    assert axo.axo_fc_dgrad(p0, A, 48, A, 48, A, 32, check=False) == OK
+    pn = axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 0)
+    assert axo.axo_fc_fwd(pn, A, 32, A, 8, None, 0, A, 8, check=False) == OK
+    assert axo.axo_fc_wgrad(pn, A, 32, A, 8, A, 8, check=False) == OK
+
+
+def test_layer_step_validates_whole_chain_first():
+    # T == 0 and N == 0: none of the three products has an output element, so nothing launches
+    good = axo.Layer(axo.Problem.make((1, 1, 1), (0, 0, 0), 0, 32, 0), 0, 0, A, 32, A, 8, None, A, 8, A, 8,
+                     A, 32, A, 8)
+    bad = axo.Layer(axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 48), 0, 0, A, 32, A, 48, None, A, 48, A, 48,
+                    None, 32, A, 48)  # dX missing
+    assert axo.axo_layer_step([], check=False) == OK
+    assert axo.axo_layer_step([good], check=False) == OK  # empty shard: no launch
+    assert axo.axo_layer_step([good, bad], check=False) == NULL_PTR
+    worse = axo.Layer(axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 48), 9, 0, A, 32, A, 48, None, A, 48, A, 48,
+                      A, 32, A, 48)
+    assert axo.axo_layer_step([worse], check=False) == BAD_EPI
+    assert axo.library().axo_layer_step(None, 2, None, 0, None) == NULL_PTR
+    assert axo.library().axo_layer_step(None, -1, None, 0, None) == BAD_ARG
+    assert axo.axo_layer_step_workspace_bytes([good, bad]) >= 0
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    import paper_2305_13525_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "_LIB_PATH", "/nonexistent/libaxo.so")
+    with pytest.raises(FileNotFoundError):
+        b.library()

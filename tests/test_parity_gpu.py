@@ -1,0 +1,241 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same
+seeded bf16 inputs.  Tolerances: relative Frobenius error <= 2e-3 and every element within
+1e-2 of its oracle row's infinity norm (gpu_util.REL_FRO_TOL / PER_ELEM_TOL).  Structured
+inputs whose products are exactly representable must match bit for bit."""
+import numpy as np
+import pytest
+
+import axo_synth as syn
+import oracle
+import paper_2305_13525_amd as axo
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import gpu_util as gu  # noqa: E402
+
+
+def P(M, Kl, Nl, grid=(1, 1, 1), coord=(0, 0, 0), transposed=0):
+    gx, gy, gz = grid
+    gk, gn = (gy, gx) if transposed else (gx, gy)
+    return axo.Problem.make(grid, coord, M * gz, Kl * gk, Nl * gn, transposed)
+
+
+def rand_trio(M, Kl, Nl, seed):
+    return (syn.normal_bf16(seed, 0, (M, Kl), 1.0), syn.normal_bf16(seed, 1, (Kl, Nl), 0.02),
+            syn.normal_bf16(seed, 2, (M, Nl), 1.0))
+
+
+def check_trio(p, Xb, Wb, dYb, tag):
+    Y, dX, dW = gu.trio(p, Xb, Wb, dYb)
+    gu.assert_close(oracle, Y, oracle.fc_fwd(Xb, Wb), tag + " fwd")
+    gu.assert_close(oracle, dX, oracle.fc_dgrad(dYb, Wb), tag + " dgrad")
+    gu.assert_close(oracle, dW, oracle.fc_wgrad(Xb, dYb), tag + " wgrad")
+    return Y, dX, dW
+
+
+def test_cfg1_unsharded_trio():
+    L = syn.configs()["cfg1"][0]
+    d = syn.layer_inputs(L)
+    p = axo.Problem.make(L.grid, (0, 0, 0), L.T, L.K, L.N)
+    check_trio(p, d["X"], d["W"], d["dY"], "cfg1")
+
+
+def test_cfg1_grid222_all_shards_and_decomposition_identity():
+    """All 8 shard trios, serially, addressed in place inside the global device tensors (leading
+    dimension > row length); each against the oracle's shard product, and the combined result
+    (sum over the K-axis, N-axis, Z-axis respectively) against the unsharded oracle product."""
+    L = syn.configs()["cfg1_grid222"][0]
+    g = syn.global_inputs(L)
+    Xg, Wg, dYg = gu.to_dev(g["X"]), gu.to_dev(g["W"]), gu.to_dev(g["dY"])
+    Ysum = np.zeros((L.T, L.N))
+    dXsum = np.zeros((L.T, L.K))
+    dWsum = np.zeros((L.K, L.N))
+    for iz in range(2):
+        for iy in range(2):
+            for ix in range(2):
+                p = axo.Problem.make(L.grid, (ix, iy, iz), L.T, L.K, L.N)
+                _, (M, Kl, Nl, r0, k0, n0) = axo.axo_shard_dims(p)
+                Xs, Ws, dYs = Xg[r0:r0 + M, k0:k0 + Kl], Wg[k0:k0 + Kl, n0:n0 + Nl], dYg[r0:r0 + M, n0:n0 + Nl]
+                Y, dX, dW = gu.empty_dev(M, Nl), gu.empty_dev(M, Kl), gu.empty_dev(Kl, Nl)
+                gu.run_fwd(p, Xs, Ws, Y)
+                gu.run_dgrad(p, dYs, Ws, dX)
+                gu.run_wgrad(p, Xs, dYs, dW)
+                torch.cuda.synchronize()
+                Xb, Wb, dYb = oracle.shards(g["X"], g["W"], g["dY"], L.grid, (ix, iy, iz))
+                tag = f"shard {ix}{iy}{iz}"
+                gu.assert_close(oracle, gu.to_host(Y), oracle.fc_fwd(Xb, Wb), tag + " fwd")
+                gu.assert_close(oracle, gu.to_host(dX), oracle.fc_dgrad(dYb, Wb), tag + " dgrad")
+                gu.assert_close(oracle, gu.to_host(dW), oracle.fc_wgrad(Xb, dYb), tag + " wgrad")
+                Ysum[r0:r0 + M, n0:n0 + Nl] += syn.bf16_bits_to_f64(gu.to_host(Y))
+                dXsum[r0:r0 + M, k0:k0 + Kl] += syn.bf16_bits_to_f64(gu.to_host(dX))
+                dWsum[k0:k0 + Kl, n0:n0 + Nl] += syn.bf16_bits_to_f64(gu.to_host(dW))
+    for got, ref, tag in ((Ysum, oracle.fc_fwd(g["X"], g["W"]), "Y"), (dXsum, oracle.fc_dgrad(g["dY"], g["W"]), "dX"),
+                          (dWsum, oracle.fc_wgrad(g["X"], g["dY"]), "dW")):
+        rel = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+        assert rel <= gu.REL_FRO_TOL, (tag, rel)
+        assert np.all(np.abs(got - ref) <= gu.PER_ELEM_TOL * np.max(np.abs(ref), axis=1, keepdims=True)), tag
+
+
+RAGGED = [(1, 8, 8), (1000, 520, 264), (130, 40, 72), (257, 264, 136), (77, 1000, 48), (45, 100, 52),
+          (129, 33, 127), (5, 7, 3), (256, 64, 256), (300, 1, 9), (128, 128, 128), (384, 96, 640)]
+
+
+@pytest.mark.parametrize("M,Kl,Nl", RAGGED)
+def test_ragged_and_tile_edge_shapes(M, Kl, Nl):
+    """Shapes that are not multiples of any tile, with padded leading dimensions where the row
+    length is not a multiple of 8."""
+    Xb, Wb, dYb = rand_trio(M, Kl, Nl, 100 + M)
+    pad = lambda n: (n + 7) // 8 * 8 + 8
+    X = torch.zeros((M, pad(Kl)), dtype=torch.int16, device="cuda:0")
+    W = torch.zeros((Kl, pad(Nl)), dtype=torch.int16, device="cuda:0")
+    dY = torch.zeros((M, pad(Nl)), dtype=torch.int16, device="cuda:0")
+    X[:, :Kl], W[:, :Nl], dY[:, :Nl] = gu.to_dev(Xb), gu.to_dev(Wb), gu.to_dev(dYb)
+    Y, dX, dW = gu.empty_dev(M, pad(Nl)), gu.empty_dev(M, pad(Kl)), gu.empty_dev(Kl, pad(Nl))
+    p = P(M, Kl, Nl)
+    gu.run_fwd(p, X[:, :Kl], W[:, :Nl], Y[:, :Nl])
+    gu.run_dgrad(p, dY[:, :Nl], W[:, :Nl], dX[:, :Kl])
+    gu.run_wgrad(p, X[:, :Kl], dY[:, :Nl], dW[:, :Nl])
+    torch.cuda.synchronize()
+    Yh, dXh, dWh = gu.to_host(Y), gu.to_host(dX), gu.to_host(dW)
+    gu.assert_close(oracle, Yh[:, :Nl], oracle.fc_fwd(Xb, Wb), "fwd")
+    gu.assert_close(oracle, dXh[:, :Kl], oracle.fc_dgrad(dYb, Wb), "dgrad")
+    gu.assert_close(oracle, dWh[:, :Nl], oracle.fc_wgrad(Xb, dYb), "wgrad")
+    # nothing outside the logical matrix was written (the pad keeps its NaN fill)
+    assert (Yh[:, Nl:] == 0x7FC0).all() and (dXh[:, Kl:] == 0x7FC0).all() and (dWh[:, Nl:] == 0x7FC0).all()
+
+
+def test_empty_dimensions():
+    # Kl == 0: forward of an empty sum is zero (then the epilogue); dW is empty
+    Xb, Wb, dYb = rand_trio(16, 8, 24, 1)
+    X, W, dY = gu.to_dev(Xb), gu.to_dev(Wb), gu.to_dev(dYb)
+    bias_b = syn.normal_bf16(1, 3, (1, 24), 0.5)[0]
+    bias = gu.to_dev(bias_b)
+    p = P(16, 0, 24)
+    Y = gu.empty_dev(16, 24)
+    gu.run_fwd(p, X[:, :0], W[:0, :], Y)
+    torch.cuda.synchronize()
+    assert not gu.to_host(Y).any()
+    gu.run_fwd(p, X[:, :0], W[:0, :], Y, bias, axo.AXO_EPI_BIAS)
+    torch.cuda.synchronize()
+    assert np.array_equal(gu.to_host(Y), np.tile(bias_b, (16, 1)))
+    # M == 0: dW of an empty sum is zero
+    p = P(0, 8, 24)
+    dW = gu.empty_dev(8, 24)
+    gu.run_wgrad(p, X[:0], dY[:0], dW)
+    torch.cuda.synchronize()
+    assert not gu.to_host(dW).any()
+    # Nl == 0: dX of an empty sum is zero
+    p = P(16, 8, 0)
+    dX = gu.empty_dev(16, 8)
+    gu.run_dgrad(p, dY[:, :0], W[:, :0], dX)
+    torch.cuda.synchronize()
+    assert not gu.to_host(dX).any()
+
+
+@pytest.mark.parametrize("epi", [axo.AXO_EPI_BIAS, axo.AXO_EPI_BIAS_GELU_TANH, axo.AXO_EPI_BIAS_GELU_ERF])
+@pytest.mark.parametrize("shape", [(200, 136, 264), (512, 256, 512)])
+def test_forward_epilogues(epi, shape):
+    M, Kl, Nl = shape
+    Xb = syn.normal_bf16(5, 0, (M, Kl), 1.0)
+    Wb = syn.normal_bf16(5, 1, (Kl, Nl), 0.1)   # pre-activations of order 1: exercises the GELU knee
+    bias_b = syn.normal_bf16(5, 3, (1, Nl), 0.5)[0]
+    X, W, bias = gu.to_dev(Xb), gu.to_dev(Wb), gu.to_dev(bias_b)
+    Y = gu.empty_dev(M, Nl)
+    gu.run_fwd(P(M, Kl, Nl), X, W, Y, bias, epi)
+    torch.cuda.synchronize()
+    gu.assert_close(oracle, gu.to_host(Y), oracle.fc_fwd(Xb, Wb, bias_b, epi), f"epi {epi}")
+
+
+def test_bias_only_at_k_coordinate_zero():
+    """On a grid whose K-splitting axis has size 2 the bias is added on coordinate 0 only, so the
+    two partial products sum to X.W + b (decomposition identity with bias)."""
+    M, K, N = 64, 128, 96
+    Xb, Wb = syn.normal_bf16(6, 0, (M, K), 1.0), syn.normal_bf16(6, 1, (K, N), 0.05)
+    bias_b = syn.normal_bf16(6, 3, (1, N), 0.5)[0]
+    Xg, Wg, bias = gu.to_dev(Xb), gu.to_dev(Wb), gu.to_dev(bias_b)
+    total = np.zeros((M, N))
+    zero_bias = np.zeros(N, dtype=np.uint16)
+    for ix in range(2):
+        p = axo.Problem.make((2, 1, 1), (ix, 0, 0), M, K, N)
+        Y = gu.empty_dev(M, N)
+        gu.run_fwd(p, Xg[:, ix * 64:(ix + 1) * 64], Wg[ix * 64:(ix + 1) * 64], Y, bias, axo.AXO_EPI_BIAS)
+        torch.cuda.synchronize()
+        ref = oracle.fc_fwd(Xb[:, ix * 64:(ix + 1) * 64], Wb[ix * 64:(ix + 1) * 64], bias_b if ix == 0 else zero_bias,
+                            oracle.EPI_BIAS)
+        gu.assert_close(oracle, gu.to_host(Y), ref, f"bias shard {ix}")
+        total += syn.bf16_bits_to_f64(gu.to_host(Y))
+    ref = oracle.fc_fwd(Xb, Wb, bias_b, oracle.EPI_BIAS)
+    assert np.linalg.norm(total - ref) <= gu.REL_FRO_TOL * np.linalg.norm(ref)
+    # transposed mapping: K is split over Gy, so iy decides
+    for iy in range(2):
+        p = axo.Problem.make((1, 2, 1), (0, iy, 0), M, K, N, 1)
+        Y = gu.empty_dev(M, N)
+        gu.run_fwd(p, Xg[:, iy * 64:(iy + 1) * 64], Wg[iy * 64:(iy + 1) * 64], Y, bias, axo.AXO_EPI_BIAS)
+        torch.cuda.synchronize()
+        ref = oracle.fc_fwd(Xb[:, iy * 64:(iy + 1) * 64], Wb[iy * 64:(iy + 1) * 64], bias_b if iy == 0 else zero_bias,
+                            oracle.EPI_BIAS)
+        gu.assert_close(oracle, gu.to_host(Y), ref, f"transposed bias shard {iy}")
+
+
+@pytest.mark.parametrize("n", [64, 256, 520])
+def test_structured_inputs_are_bit_exact(n):
+    one = np.uint16(0x3F80)
+    Xb = syn.normal_bf16(8, 0, (n + 40, n), 1.0)
+    eye = np.zeros((n, n), dtype=np.uint16)
+    eye[np.arange(n), np.arange(n)] = one
+    p = P(n + 40, n, n)
+    Y, dX, dW = gu.trio(p, Xb, eye, Xb)
+    assert np.array_equal(Y, Xb), "X . I must reproduce X bit for bit"
+    assert np.array_equal(dX, Xb), "dY . I^T must reproduce dY bit for bit"
+    # one-hot X row: forward picks (a power-of-two multiple of) one row of W
+    Wb = syn.normal_bf16(8, 1, (n, n), 0.02)
+    hot = np.zeros((n + 40, n), dtype=np.uint16)
+    hot[n + 39, n - 1] = np.uint16(0x4000)  # 2.0 in the last row / last column
+    hot[0, 0] = np.uint16(0x3F00)           # 0.5
+    Y, _, dW = gu.trio(p, hot, Wb, Xb)
+    assert np.array_equal(syn.bf16_bits_to_f64(Y[n + 39]), 2.0 * syn.bf16_bits_to_f64(Wb[n - 1]))
+    assert np.array_equal(syn.bf16_bits_to_f64(Y[0]), 0.5 * syn.bf16_bits_to_f64(Wb[0]))
+    assert not syn.bf16_bits_to_f64(Y[1:n + 39]).any()
+    # wgrad of the one-hot X: row n-1 of dW is 2 * dY[last], row 0 is 0.5 * dY[0], the rest zero
+    assert np.array_equal(syn.bf16_bits_to_f64(dW[n - 1]), 2.0 * syn.bf16_bits_to_f64(Xb[n + 39]))
+    assert np.array_equal(syn.bf16_bits_to_f64(dW[0]), 0.5 * syn.bf16_bits_to_f64(Xb[0]))
+    assert not syn.bf16_bits_to_f64(dW[1:n - 1]).any()
+
+
+def test_adjoint_identity_on_gpu_results():
+    M, Kl, Nl = 384, 320, 448
+    Xb, Wb, dYb = rand_trio(M, Kl, Nl, 9)
+    Y, dX, dW = (syn.bf16_bits_to_f64(a) for a in gu.trio(P(M, Kl, Nl), Xb, Wb, dYb))
+    Xf, Wf, Gf = (syn.bf16_bits_to_f64(a) for a in (Xb, Wb, dYb))
+    a, b, c = np.sum(Gf * Y), np.sum(dX * Xf), np.sum(dW * Wf)
+    scale = np.linalg.norm(Gf) * np.linalg.norm(Y)
+    assert abs(a - b) <= 1e-3 * scale and abs(a - c) <= 1e-3 * scale
+
+
+def test_results_are_reproducible_run_to_run():
+    M, Kl, Nl = 512, 768, 256
+    Xb, Wb, dYb = rand_trio(M, Kl, Nl, 10)
+    r1 = gu.trio(P(M, Kl, Nl), Xb, Wb, dYb)
+    r2 = gu.trio(P(M, Kl, Nl), Xb, Wb, dYb)
+    for a, b in zip(r1, r2):
+        assert np.array_equal(a, b)
+
+
+def test_rounding_is_nearest_even():
+    """Products chosen to land exactly on bf16 rounding ties: X row = [1, 2^-8], W col = [1, t]."""
+    n = 64
+    X = np.zeros((n, n), dtype=np.uint16)
+    W = np.zeros((n, n), dtype=np.uint16)
+    X[:, 0] = 0x3F80             # 1.0
+    X[:, 1] = 0x3B80             # 2^-8
+    W[0, :] = 0x3F80             # 1.0
+    W[1, 0::4] = 0x3F80          # 1 + 2^-8  -> tie, rounds to even 1.0         (0x3F80)
+    W[1, 1::4] = 0x4040          # 1 + 3*2^-8 -> rounds to nearest 1 + 2^-6 ... (checked against the oracle)
+    W[1, 2::4] = 0x3FC0          # 1 + 1.5*2^-8
+    W[1, 3::4] = 0x0000
+    Y, _, _ = gu.trio(P(n, n, n), X, W, X)
+    ref = oracle.fc_fwd(X, W)
+    want = syn.f32_to_bf16_bits(ref.astype(np.float32))  # every sum here is exact in fp32
+    assert np.array_equal(Y, want)
+    assert Y[0, 0] == 0x3F80 and Y[0, 3] == 0x3F80
