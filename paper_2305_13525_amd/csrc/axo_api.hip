@@ -5,10 +5,13 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+#include <cstdlib>
 #include <new>
 
 #include "axo_common.hpp"
 #include "gemm_generic.hpp"
+#include "gemm_tile.hpp"
 
 namespace {
 
@@ -54,8 +57,7 @@ int check_matrix(const void* ptr, int64_t ld, int64_t rows, int64_t row_len) {
     return AXO_OK;
 }
 
-int launch(const GemmArgs& g, int la, int lb, hipStream_t st) {
-    if (g.Mo == 0 || g.No == 0) return AXO_OK;
+int launch_generic(const GemmArgs& g, int la, int lb, hipStream_t st) {
     dim3 grid((g.No + axo::GEN_BN - 1) / axo::GEN_BN, (g.Mo + axo::GEN_BM - 1) / axo::GEN_BM, 1);
     dim3 block(256, 1, 1);
     if (grid.y > 65535u) return AXO_ERR_BAD_SIZE;
@@ -66,6 +68,45 @@ int launch(const GemmArgs& g, int la, int lb, hipStream_t st) {
     else
         hipLaunchKernelGGL((axo::gemm_generic_kernel<axo::MC, axo::MC>), grid, block, 0, st, g);
     return hipGetLastError() == hipSuccess ? AXO_OK : AXO_ERR_HIP;
+}
+
+// Launch of one tuned-kernel instantiation.  The dynamic LDS size is above the default limit, so
+// the attribute is raised once per instantiation (per process; one device per process).
+template <int BM, int BN, int WGM, int WGN, int LA, int LB>
+int launch_tile(const GemmArgs& g, hipStream_t st) {
+    using Cfg = axo::TileCfg<BM, BN, WGM, WGN, LA, LB>;
+    auto kern = axo::gemm_tile_kernel<BM, BN, WGM, WGN, LA, LB>;
+    static std::atomic<int> ready{0};
+    if (!ready.load(std::memory_order_acquire)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                Cfg::LDS_BYTES) != hipSuccess)
+            return AXO_ERR_HIP;
+        ready.store(1, std::memory_order_release);
+    }
+    const int tiles_m = g.Mo / BM, tiles_n = g.No / BN;
+    const int group_m = tiles_m < 4 ? tiles_m : 4;
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(axo::TILE_THREADS), Cfg::LDS_BYTES, st, g, tiles_m, tiles_n,
+                       group_m);
+    return hipGetLastError() == hipSuccess ? AXO_OK : AXO_ERR_HIP;
+}
+
+template <int BM, int BN, int WGM, int WGN>
+int launch_tile_layout(const GemmArgs& g, int la, int lb, hipStream_t st) {
+    if (la == axo::KC && lb == axo::MC) return launch_tile<BM, BN, WGM, WGN, axo::KC, axo::MC>(g, st);
+    if (la == axo::KC && lb == axo::KC) return launch_tile<BM, BN, WGM, WGN, axo::KC, axo::KC>(g, st);
+    return launch_tile<BM, BN, WGM, WGN, axo::MC, axo::MC>(g, st);
+}
+
+bool force_generic() {
+    static const bool v = [] { const char* e = getenv("AXO_FORCE_GENERIC"); return e && e[0] == '1'; }();
+    return v;
+}
+
+int launch(const GemmArgs& g, int la, int lb, hipStream_t st) {
+    if (g.Mo == 0 || g.No == 0) return AXO_OK;
+    const bool tileable = g.R > 0 && g.R % axo::TILE_BK == 0 && g.Mo % 256 == 0 && g.No % 256 == 0;
+    if (tileable && !force_generic()) return launch_tile_layout<256, 256, 2, 4>(g, la, lb, st);
+    return launch_generic(g, la, lb, st);
 }
 
 // Validated, launch-ready description of one product.

@@ -203,6 +203,46 @@ def test_structured_inputs_are_bit_exact(n):
     assert not syn.bf16_bits_to_f64(dW[1:n - 1]).any()
 
 
+TILED = [(512, 192, 768), (256, 64, 512), (768, 448, 256), (1024, 128, 1280), (256, 2048, 256)]
+
+
+@pytest.mark.parametrize("M,Kl,Nl", TILED)
+def test_tile_multiple_shapes(M, Kl, Nl):
+    """Shapes that are whole multiples of the tuned kernel's tile in all three roles, several tiles
+    wide and high, with different extents per dimension so that a swapped index cannot cancel."""
+    Xb, Wb, dYb = rand_trio(M, Kl, Nl, 200 + Kl)
+    check_trio(P(M, Kl, Nl), Xb, Wb, dYb, f"tiled {M}x{Kl}x{Nl}")
+
+
+def test_tile_multiple_shapes_in_place_and_structured():
+    """Tuned-kernel shapes addressed inside larger buffers (leading dimension > row length), and an
+    identity weight that must reproduce the activation bit for bit."""
+    M, Kl, Nl = 512, 256, 768
+    Xb, Wb, dYb = rand_trio(M, Kl, Nl, 31)
+    big = lambda r, c: torch.zeros((r, c + 64), dtype=torch.int16, device="cuda:0")
+    X, W, dY = big(M, Kl), big(Kl, Nl), big(M, Nl)
+    X[:, 8:8 + Kl], W[:, 16:16 + Nl], dY[:, 24:24 + Nl] = gu.to_dev(Xb), gu.to_dev(Wb), gu.to_dev(dYb)
+    Y, dX, dW = gu.empty_dev(M, Nl + 64), gu.empty_dev(M, Kl + 64), gu.empty_dev(Kl, Nl + 64)
+    p = P(M, Kl, Nl)
+    gu.run_fwd(p, X[:, 8:8 + Kl], W[:, 16:16 + Nl], Y[:, 32:32 + Nl])
+    gu.run_dgrad(p, dY[:, 24:24 + Nl], W[:, 16:16 + Nl], dX[:, 8:8 + Kl])
+    gu.run_wgrad(p, X[:, 8:8 + Kl], dY[:, 24:24 + Nl], dW[:, 40:40 + Nl])
+    torch.cuda.synchronize()
+    Yh, dXh, dWh = gu.to_host(Y), gu.to_host(dX), gu.to_host(dW)
+    gu.assert_close(oracle, Yh[:, 32:32 + Nl], oracle.fc_fwd(Xb, Wb), "fwd")
+    gu.assert_close(oracle, dXh[:, 8:8 + Kl], oracle.fc_dgrad(dYb, Wb), "dgrad")
+    gu.assert_close(oracle, dWh[:, 40:40 + Nl], oracle.fc_wgrad(Xb, dYb), "wgrad")
+    assert (Yh[:, :32] == 0x7FC0).all() and (Yh[:, 32 + Nl:] == 0x7FC0).all()
+    assert (dXh[:, :8] == 0x7FC0).all() and (dXh[:, 8 + Kl:] == 0x7FC0).all()
+    assert (dWh[:, :40] == 0x7FC0).all() and (dWh[:, 40 + Nl:] == 0x7FC0).all()
+    n = 512
+    eye = np.zeros((n, n), dtype=np.uint16)
+    eye[np.arange(n), np.arange(n)] = 0x3F80
+    Xs = syn.normal_bf16(32, 0, (768, n), 1.0)
+    Y2, dX2, dW2 = gu.trio(P(768, n, n), Xs, eye, Xs)
+    assert np.array_equal(Y2, Xs) and np.array_equal(dX2, Xs)
+
+
 def test_adjoint_identity_on_gpu_results():
     M, Kl, Nl = 384, 320, 448
     Xb, Wb, dYb = rand_trio(M, Kl, Nl, 9)
