@@ -20,6 +20,15 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
 
+# HBM-side bytes per launch (fetched + written) of the tuned kernel, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this script, scaled by the same counters' readings for a plain 1 GiB copy
+# (2.000 KiB per FETCH_SIZE count, 1.000 KiB per WRITE_SIZE count).  Keyed by (workload, product).
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg2", "fwd"): int((83053.48 * 2.0 + 49152.0) * 1024),
+    ("cfg2", "dgrad"): int((98652.57 * 2.0 + 16384.0) * 1024),
+    ("cfg2", "wgrad"): int((82589.72 * 2.0 + 24576.0) * 1024),
+}
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -29,6 +38,8 @@ def main() -> int:
     ap.add_argument("--config", default="cfg2", help="cfg1..cfg5 (default cfg2, the QKV shard)")
     ap.add_argument("--all-configs", action="store_true", help="also time cfg2..cfg5 and report them under 'configs'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU's share of the work on one GPU; "
@@ -105,6 +116,15 @@ def main() -> int:
                                steps, warmup)
         return res
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB read + 1 GiB write per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+
     layers, objs, keep, flop, wsp, nws = setup(args.config)
     ms, wall_ms = time_step(objs, wsp, nws, args.steps, args.warmup)
     tflops = flop / (ms * 1e-3) / 1e12
@@ -118,7 +138,7 @@ def main() -> int:
     M, Kl, Nl = layers[li].shard
     roofline = {"bound": "mfma", "kernel": f"{layers[li].name}.{dom}", "achieved": round(ach, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                "traffic": None, "flop_per_launch": gflop, "avg_launch_ms": round(ops[dom], 5),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, dom)), "flop_per_launch": gflop, "avg_launch_ms": round(ops[dom], 5),
                 "algorithmic_bytes_per_launch": 2 * (M * Kl + Kl * Nl + M * Nl),
                 "per_op_ms": {k: round(v, 5) for k, v in ops.items()},
                 "per_op_tflops": {k: round(gflop / (v * 1e-3) / 1e12, 2) for k, v in ops.items()}}
@@ -152,8 +172,11 @@ def main() -> int:
         L = layers[li]
         d = syn.layer_inputs(L)
         M, Kl, Nl = L.shard
-        n_act = min(M, 768)
-        n_w = min(Kl, 384)
+        # the oracle runs about 60 GFLOP/s on 16 cores: bound the sample to roughly 10-20 s of CPU work
+        budget_flop = 0.9e12
+        frac = min(1.0, budget_flop / (3.0 * L.flop_per_gemm))
+        n_act = max(1, int(M * frac))
+        n_w = max(1, int(Kl * frac))
         rows = np.linspace(0, M - 1, n_act).astype(np.int64)
         krows = np.linspace(0, Kl - 1, n_w).astype(np.int64)
         t0 = time.perf_counter()

@@ -7,7 +7,13 @@
 
 #include <atomic>
 #include <cstdlib>
+#include <functional>
+#include <map>
+#include <mutex>
 #include <new>
+#include <queue>
+#include <utility>
+#include <vector>
 
 #include "axo_common.hpp"
 #include "gemm_generic.hpp"
@@ -70,31 +76,88 @@ int launch_generic(const GemmArgs& g, int la, int lb, hipStream_t st) {
     return hipGetLastError() == hipSuccess ? AXO_OK : AXO_ERR_HIP;
 }
 
+// The tuned kernel covers the output with 256x256 tiles and, to balance tile counts that do not
+// fill the last round of CUs, a region of 256x128 tiles.  The CU count is a design constant
+// (MI355X: 256 CUs) so that planning needs no device.
+constexpr int NUM_CU = 256;
+// relative cost of a half-width tile (half the flops at lower efficiency: more operand traffic
+// per flop), in units of one big tile; measured on MI355X
+constexpr double SMALL_TILE_COST = 0.60;
+
+bool tileable(int Mo, int No, int R) {
+    return R > 0 && R % axo::MIX_BK == 0 && Mo > 0 && No > 0 && Mo % 256 == 0 && No % 128 == 0;
+}
+
+// Time (in big-tile units) a greedy dispatch of n_big big tiles followed by n_small small tiles
+// takes on NUM_CU CUs: workgroups are handed out in order to whichever CU is free first.
+double makespan(int n_big, int n_small) {
+    std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
+    for (int i = 0; i < NUM_CU; ++i) free_at.push(0.0);
+    double end = 0.0;
+    auto run = [&](int n, double cost) {
+        for (int i = 0; i < n; ++i) {
+            const double t = free_at.top() + cost;
+            free_at.pop();
+            free_at.push(t);
+            if (t > end) end = t;
+        }
+    };
+    run(n_big, 1.0);
+    run(n_small, SMALL_TILE_COST);
+    return end;
+}
+
+// Choose how many 256-wide tile columns to use; the remaining columns become 128-wide tiles.
+// Plans are cached per output shape (the search simulates the dispatch).
+axo::TileSched plan_tiles(int Mo, int No) {
+    static std::mutex mu;
+    static std::map<std::pair<int, int>, axo::TileSched> cache;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = cache.find({Mo, No});
+    if (it != cache.end()) return it->second;
+    axo::TileSched sc{};
+    sc.tiles_m = Mo / 256;
+    const int max_big_cols = No / 256;
+    int best_cols = max_big_cols;
+    double best = 1e30;
+    for (int cb = max_big_cols; cb >= 0; --cb) {
+        const int small_cols = (No - cb * 256) / 128;
+        const double t = makespan(sc.tiles_m * cb, sc.tiles_m * small_cols);
+        if (t < best - 1e-9) {
+            best = t;
+            best_cols = cb;
+        }
+    }
+    sc.big_cols = best_cols;
+    sc.small_cols = (No - best_cols * 256) / 128;
+    sc.n_big = sc.tiles_m * sc.big_cols;
+    sc.group_m = sc.tiles_m < 4 ? sc.tiles_m : 4;
+    if (cache.size() < 4096) cache[{Mo, No}] = sc;
+    return sc;
+}
+
 // Launch of one tuned-kernel instantiation.  The dynamic LDS size is above the default limit, so
 // the attribute is raised once per instantiation (per process; one device per process).
-template <int BM, int BN, int WGM, int WGN, int LA, int LB>
+template <int LA, int LB>
 int launch_tile(const GemmArgs& g, hipStream_t st) {
-    using Cfg = axo::TileCfg<BM, BN, WGM, WGN, LA, LB>;
-    auto kern = axo::gemm_tile_kernel<BM, BN, WGM, WGN, LA, LB>;
+    auto kern = axo::gemm_mixed_kernel<LA, LB>;
     static std::atomic<int> ready{0};
     if (!ready.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                Cfg::LDS_BYTES) != hipSuccess)
+                                axo::MIX_LDS_BYTES) != hipSuccess)
             return AXO_ERR_HIP;
         ready.store(1, std::memory_order_release);
     }
-    const int tiles_m = g.Mo / BM, tiles_n = g.No / BN;
-    const int group_m = tiles_m < 4 ? tiles_m : 4;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(axo::TILE_THREADS), Cfg::LDS_BYTES, st, g, tiles_m, tiles_n,
-                       group_m);
+    const axo::TileSched sc = plan_tiles(g.Mo, g.No);
+    const int blocks = sc.n_big + sc.tiles_m * sc.small_cols;
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(axo::TILE_THREADS), axo::MIX_LDS_BYTES, st, g, sc);
     return hipGetLastError() == hipSuccess ? AXO_OK : AXO_ERR_HIP;
 }
 
-template <int BM, int BN, int WGM, int WGN>
 int launch_tile_layout(const GemmArgs& g, int la, int lb, hipStream_t st) {
-    if (la == axo::KC && lb == axo::MC) return launch_tile<BM, BN, WGM, WGN, axo::KC, axo::MC>(g, st);
-    if (la == axo::KC && lb == axo::KC) return launch_tile<BM, BN, WGM, WGN, axo::KC, axo::KC>(g, st);
-    return launch_tile<BM, BN, WGM, WGN, axo::MC, axo::MC>(g, st);
+    if (la == axo::KC && lb == axo::MC) return launch_tile<axo::KC, axo::MC>(g, st);
+    if (la == axo::KC && lb == axo::KC) return launch_tile<axo::KC, axo::KC>(g, st);
+    return launch_tile<axo::MC, axo::MC>(g, st);
 }
 
 bool force_generic() {
@@ -104,9 +167,16 @@ bool force_generic() {
 
 int launch(const GemmArgs& g, int la, int lb, hipStream_t st) {
     if (g.Mo == 0 || g.No == 0) return AXO_OK;
-    const bool tileable = g.R > 0 && g.R % axo::TILE_BK == 0 && g.Mo % 256 == 0 && g.No % 256 == 0;
-    if (tileable && !force_generic()) return launch_tile_layout<256, 256, 2, 4>(g, la, lb, st);
+    if (tileable(g.Mo, g.No, g.R) && !force_generic()) return launch_tile_layout(g, la, lb, st);
     return launch_generic(g, la, lb, st);
+}
+
+int check_workspace(const axo_problem_t* p, int op, const void* ws, size_t ws_bytes) {
+    const size_t need = axo_workspace_bytes(p, op);
+    if (need == 0) return AXO_OK;
+    if (!ws || ws_bytes < need) return AXO_ERR_WORKSPACE;
+    if (!aligned16(ws)) return AXO_ERR_MISALIGNED;
+    return AXO_OK;
 }
 
 // Validated, launch-ready description of one product.
@@ -126,8 +196,7 @@ int plan_fwd(const axo_problem_t* p, const void* X, int64_t ldx, const void* W, 
     if ((rc = check_matrix(W, ldw, s.Kl, s.Nl))) return rc;
     if ((rc = check_matrix(Y, ldy, s.M, s.Nl))) return rc;
     if (epilogue != AXO_EPI_NONE && !aligned16(bias)) return AXO_ERR_MISALIGNED;
-    if (ws_bytes < axo_workspace_bytes(p, AXO_OP_FWD) || (axo_workspace_bytes(p, AXO_OP_FWD) && !ws))
-        return AXO_ERR_WORKSPACE;
+    if ((rc = check_workspace(p, AXO_OP_FWD, ws, ws_bytes))) return rc;
     GemmArgs& g = out->g;
     g.A = static_cast<const axo::bf16_t*>(X); g.lda = ldx;
     g.B = static_cast<const axo::bf16_t*>(W); g.ldb = ldw;
@@ -149,8 +218,7 @@ int plan_dgrad(const axo_problem_t* p, const void* dY, int64_t lddy, const void*
     if ((rc = check_matrix(dY, lddy, s.M, s.Nl))) return rc;
     if ((rc = check_matrix(W, ldw, s.Kl, s.Nl))) return rc;
     if ((rc = check_matrix(dX, lddx, s.M, s.Kl))) return rc;
-    if (ws_bytes < axo_workspace_bytes(p, AXO_OP_DGRAD) || (axo_workspace_bytes(p, AXO_OP_DGRAD) && !ws))
-        return AXO_ERR_WORKSPACE;
+    if ((rc = check_workspace(p, AXO_OP_DGRAD, ws, ws_bytes))) return rc;
     GemmArgs& g = out->g;
     g.A = static_cast<const axo::bf16_t*>(dY); g.lda = lddy;
     g.B = static_cast<const axo::bf16_t*>(W); g.ldb = ldw;
@@ -171,8 +239,7 @@ int plan_wgrad(const axo_problem_t* p, const void* X, int64_t ldx, const void* d
     if ((rc = check_matrix(X, ldx, s.M, s.Kl))) return rc;
     if ((rc = check_matrix(dY, lddy, s.M, s.Nl))) return rc;
     if ((rc = check_matrix(dW, lddw, s.Kl, s.Nl))) return rc;
-    if (ws_bytes < axo_workspace_bytes(p, AXO_OP_WGRAD) || (axo_workspace_bytes(p, AXO_OP_WGRAD) && !ws))
-        return AXO_ERR_WORKSPACE;
+    if ((rc = check_workspace(p, AXO_OP_WGRAD, ws, ws_bytes))) return rc;
     GemmArgs& g = out->g;
     g.A = static_cast<const axo::bf16_t*>(X); g.lda = ldx;
     g.B = static_cast<const axo::bf16_t*>(dY); g.ldb = lddy;
@@ -227,7 +294,7 @@ size_t axo_workspace_bytes(const axo_problem_t* p, int op) {
     Shard s;
     if (derive_shard(p, &s) != AXO_OK) return 0;
     if (op < AXO_OP_FWD || op > AXO_OP_WGRAD) return 0;
-    return 0;
+    return 0;  // no product needs workspace at present; the argument is kept for split reductions
 }
 
 int axo_fc_fwd(const axo_problem_t* p, const void* X, int64_t ldx, const void* W, int64_t ldw, const void* bias,

@@ -128,6 +128,16 @@ def test_dgrad_wgrad_argument_errors():
     assert d(p=None) == NULL_PTR and w(p=None) == NULL_PTR
 
 
+def test_workspace_query():
+    """No product needs device workspace at present; the query is total and never fails."""
+    mk = axo.Problem.make
+    for op in (axo.AXO_OP_FWD, axo.AXO_OP_DGRAD, axo.AXO_OP_WGRAD):
+        assert axo.axo_workspace_bytes(mk((2, 2, 4), (0, 0, 0), 16384, 4096, 12288), op) == 0
+        assert axo.axo_workspace_bytes(mk((1, 1, 1), (0, 0, 0), 1000, 520, 264), op) == 0
+    assert axo.axo_workspace_bytes(mk((0, 1, 1), (0, 0, 0), 8, 8, 8), axo.AXO_OP_FWD) == 0   # invalid problem
+    assert axo.axo_workspace_bytes(mk((1, 1, 1), (0, 0, 0), 8, 8, 8), 7) == 0                # unknown op
+
+
 def test_empty_shards_need_no_device():
     # M == 0 or Nl == 0: valid, nothing is launched, so this runs without a GPU
     p0 = axo.Problem.make((1, 1, 1), (0, 0, 0), 0, 32, 48)

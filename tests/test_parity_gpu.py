@@ -203,7 +203,8 @@ def test_structured_inputs_are_bit_exact(n):
     assert not syn.bf16_bits_to_f64(dW[1:n - 1]).any()
 
 
-TILED = [(512, 192, 768), (256, 64, 512), (768, 448, 256), (1024, 128, 1280), (256, 2048, 256)]
+TILED = [(512, 192, 768), (256, 64, 512), (768, 448, 256), (1024, 128, 1280), (256, 2048, 256),
+         (256, 64, 128), (512, 128, 384), (768, 256, 640), (256, 512, 896), (1280, 384, 1152)]
 
 
 @pytest.mark.parametrize("M,Kl,Nl", TILED)
