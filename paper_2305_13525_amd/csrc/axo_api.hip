@@ -84,8 +84,17 @@ constexpr int NUM_CU = 256;
 // per flop), in units of one big tile; measured on MI355X
 constexpr double SMALL_TILE_COST = 0.60;
 
-bool tileable(int Mo, int No, int R) {
-    return R > 0 && R % axo::MIX_BK == 0 && Mo > 0 && No > 0 && Mo % 256 == 0 && No % 128 == 0;
+// The tuned kernel addresses an operand tile through a buffer descriptor with 32-bit byte offsets:
+// the span a workgroup walks (256 rows of a KC operand, or the whole reduction of an MC operand)
+// has to stay below 4 GiB.
+bool span_ok(int layout, int64_t ld, int R) {
+    const int64_t elems = layout == axo::KC ? 256 * ld + R : (int64_t)R * ld + 256;
+    return elems * 2 < (int64_t)0xFFFF0000;
+}
+
+bool tileable(const GemmArgs& g, int la, int lb) {
+    return g.R > 0 && g.R % (2 * axo::TILE_BK) == 0 && g.Mo > 0 && g.No > 0 && g.Mo % 256 == 0 && g.No % 128 == 0 &&
+           span_ok(la, g.lda, g.R) && span_ok(lb, g.ldb, g.R);
 }
 
 // Time (in big-tile units) a greedy dispatch of n_big big tiles followed by n_small small tiles
@@ -167,7 +176,7 @@ bool force_generic() {
 
 int launch(const GemmArgs& g, int la, int lb, hipStream_t st) {
     if (g.Mo == 0 || g.No == 0) return AXO_OK;
-    if (tileable(g.Mo, g.No, g.R) && !force_generic()) return launch_tile_layout(g, la, lb, st);
+    if (tileable(g, la, lb) && !force_generic()) return launch_tile_layout(g, la, lb, st);
     return launch_generic(g, la, lb, st);
 }
 

@@ -1,20 +1,27 @@
 // Tuned bf16 MFMA GEMM for gfx950 (MI355X) for shapes that are whole multiples of the tile:
-//   C[Mo x No] = sum_r A(i, r) * B(j, r),  Mo % BM == 0, No % BN == 0, R % BK == 0.
+//   C[Mo x No] = sum_r A(i, r) * B(j, r),  Mo % 256 == 0, No % 128 == 0, R % 128 == 0.
 // Tile counts that do not fill the last round of CUs are balanced by covering part of the output
 // with half-width tiles (TileSched).
 //
 // One 512-thread workgroup (8 waves, two per SIMD) owns a BM x BN output tile and walks the
-// reduction in steps of BK (32 or 64) through a ring of STAGES LDS buffers.  Operand tiles are copied
-// global -> LDS by the direct-to-LDS load (16 bytes per lane, no register staging); STAGES-1
-// steps are in flight while one is being read, which is what hides the ~1.4 us loaded memory
-// latency (a two-deep buffer keeps only one step in flight and is latency bound).  MFMA 32x32x16
-// fragments are read from LDS with ds_read_b128 when the reduction index is contiguous in memory
-// (KC) and with the transposing ds_read_b64_tr_b16 when the output index is contiguous (MC), so
-// no operand is ever transposed in global memory.  16-byte chunks are permuted on their way into
-// LDS (the lane chooses which global chunk it fetches) so that fragment reads are spread over
-// the banks.  The accumulators hold the transposed 32x32 tile (B fragment first), which gives
-// each lane 4 consecutive output columns; the epilogue rounds to bf16 once, stages the wave's
-// sub-tile through LDS and writes full 128-byte row segments.
+// reduction in steps of 64 through two LDS stages.  Operand tiles are copied global -> LDS by
+// direct-to-LDS buffer loads (16 bytes per lane, no register staging).  MFMA 32x32x16 fragments
+// are read from LDS with ds_read_b128 when the reduction index is contiguous in memory (KC) and
+// with the transposing ds_read_b64_tr_b16 when the output index is contiguous (MC), so no operand
+// is ever transposed in global memory.  16-byte chunks are permuted on their way into LDS (the
+// lane chooses which global chunk it fetches) so that fragment reads are spread over the banks.
+//
+// The steady-state loop contains no vector ALU work at all: measurements showed that every VALU
+// instruction (64-bit address arithmetic above all) takes issue slots from the MFMAs of the same
+// SIMD.  Global addresses are a buffer descriptor per operand tile, a per-lane byte offset computed
+// once, and a scalar offset that advances with the reduction step; LDS fragment addresses are
+// per-lane registers computed once per stage, with the tile / sub-step part in the instruction's
+// immediate offset; the loop is unrolled over the two stages so that nothing depends on the
+// stage index at run time.
+//
+// The accumulators hold the transposed 32x32 tile (B fragment first), which gives each lane 4
+// consecutive output columns; the epilogue rounds to bf16 once, stages the wave's sub-tile through
+// LDS and writes full 128-byte row segments.
 #pragma once
 #include <type_traits>
 
@@ -23,19 +30,26 @@
 namespace axo {
 
 constexpr int TILE_THREADS = 512;
+constexpr int TILE_BK = 64;
 constexpr int NUM_XCD = 8;
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
+#ifndef AXO_PRIO
+#define AXO_PRIO 1
+#endif
+#if AXO_PRIO
+#define AXO_SETPRIO(n) __builtin_amdgcn_s_setprio(n)
+#else
+#define AXO_SETPRIO(n)
+#endif
 #ifndef AXO_SCHED
 #define AXO_SCHED 1
 #endif
 
-// KC tile in LDS: row r is BK*2 bytes = BK/8 chunks of 16 bytes, chunk c stored at
-// c ^ ((r / 2) % 8) for BK = 64 and c ^ ((r / 4) % 4) for BK = 32: 16 consecutive rows read at
-// the same c then hit 16 different 16-byte bank groups.
-template <int BK>
-__device__ __forceinline__ int swz_kc(int r) { return BK == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3); }
+// KC tile in LDS: row r is 128 bytes = 8 chunks of 16 bytes, chunk c stored at c ^ ((r / 2) % 8):
+// 16 consecutive rows read at the same c then hit 16 different 16-byte bank groups.
+__device__ __forceinline__ int swz_kc(int r) { return (r >> 1) & 7; }
 // MC tile in LDS: reduction row k is ROWS*2 bytes, chunk c stored at c ^ 4*(k % 4): the four
 // reduction rows one transposing read touches land in different bank groups.
 __device__ __forceinline__ int swz_mc(int k) { return (k & 3) << 2; }
@@ -73,85 +87,105 @@ __device__ __forceinline__ void tile_of_index(int t, int tiles_m, int tiles_n, i
     tn = in_band / gm;
 }
 
-template <int BM, int BN, int WGM, int WGN, int BK, int STAGES>
+template <int BM, int BN, int WGM, int WGN>
 struct TileCfg {
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
     static constexpr int TM = WTM / 32, TN = WTN / 32;    // MFMA tiles per wave
-    static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+    static constexpr int A_BYTES = BM * TILE_BK * 2, B_BYTES = BN * TILE_BK * 2;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int A_ROUNDS = BM * (BK / 8) / TILE_THREADS, B_ROUNDS = BN * (BK / 8) / TILE_THREADS;
+    static constexpr int A_ROUNDS = BM * (TILE_BK / 8) / TILE_THREADS, B_ROUNDS = BN * (TILE_BK / 8) / TILE_THREADS;
     static constexpr int LOADS_PER_STAGE = A_ROUNDS + B_ROUNDS;
     static constexpr int EPI_STRIDE = WTN * 2 + 16;  // bytes per staged row (padded)
     static constexpr int EPI_BYTES = 8 * WTM * EPI_STRIDE;
-    static constexpr int RING_BYTES = STAGES * STAGE_BYTES;
+    static constexpr int RING_BYTES = 2 * STAGE_BYTES;
     static constexpr int LDS_BYTES = (RING_BYTES > EPI_BYTES) ? RING_BYTES : EPI_BYTES;
     static_assert(WGM * WGN == 8, "8 waves");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 MFMA tiles");
-    static_assert(BK == 32 || BK == 64, "reduction step");
-    static_assert((BM * (BK / 8)) % TILE_THREADS == 0 && (BN * (BK / 8)) % TILE_THREADS == 0, "whole load rounds");
-    static_assert(STAGES >= 2, "at least one step in flight");
+    static_assert((BM * (TILE_BK / 8)) % TILE_THREADS == 0 && (BN * (TILE_BK / 8)) % TILE_THREADS == 0, "whole load rounds");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
-    static_assert(LOADS_PER_STAGE * (STAGES - 1) < 64, "vmcnt is 6 bits");
 };
 
-// Per-thread addressing of one operand tile's global -> LDS copy: for each round the element
-// offset of the 16-byte chunk this lane fetches (relative to the tile origin at reduction step 0).
-template <int ROWS, int LAYOUT, int BK, int ROUNDS>
-__device__ __forceinline__ void load_offsets(int tid, int64_t ld, int64_t* off) {
+// Per-lane byte offset (from the operand tile's origin at reduction step 0) of the 16-byte chunk
+// this lane fetches in each load round.  Must stay below 2^32 (checked on the host).
+template <int ROWS, int LAYOUT, int ROUNDS>
+__device__ __forceinline__ void load_offsets(int tid, int64_t ld, uint32_t* off) {
 #pragma unroll
     for (int j = 0; j < ROUNDS; ++j) {
         const int q = j * TILE_THREADS + tid;
         if (LAYOUT == KC) {
-            constexpr int CPR = BK / 8;  // chunks per row
+            constexpr int CPR = TILE_BK / 8;  // chunks per row
             const int r = q / CPR, cs = q % CPR;
-            off[j] = (int64_t)r * ld + ((cs ^ swz_kc<BK>(r)) << 3);
+            off[j] = (uint32_t)(((int64_t)r * ld + ((cs ^ swz_kc(r)) << 3)) * 2);
         } else {
             constexpr int CPR = ROWS / 8;  // chunks per reduction row
             const int k = q / CPR, cs = q % CPR;
-            off[j] = (int64_t)k * ld + ((cs ^ swz_mc(k)) << 3);
+            off[j] = (uint32_t)(((int64_t)k * ld + ((cs ^ swz_mc(k)) << 3)) * 2);
         }
     }
 }
 
+// Copies one operand tile of one reduction step into LDS: round j of wave w lands at
+// lds_tile + (j * 512 + w * 64 + lane) * 16.  `soff` is the scalar byte offset of the step.
 template <int ROUNDS>
-__device__ __forceinline__ void issue_loads(const bf16_t* base, const int64_t* off, char* lds_tile, int wave) {
+__device__ __forceinline__ void issue_loads(__amdgpu_buffer_rsrc_t rsrc, const uint32_t* off, uint32_t soff,
+                                            char* lds_tile, int wave) {
 #pragma unroll
     for (int j = 0; j < ROUNDS; ++j) {
         char* dst = lds_tile + (j * TILE_THREADS + wave * 64) * 16;
-        __builtin_amdgcn_global_load_lds(base + off[j], (lds_void_ptr)dst, 16, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)dst, 16, off[j], soff, 0, 0);
     }
 }
 
-// Fragment (8 consecutive reduction elements of one output row/column per lane) for the MFMA
-// tile whose first row is row0, at reduction sub-step kk (16 elements each; BK/16 per stage).
-template <int ROWS, int LAYOUT, int BK>
-__device__ __forceinline__ bf16x8 read_fragment(const char* lds_tile, int row0, int kk, int lane) {
-    if (LAYOUT == KC) {
-        const int r = row0 + (lane & 31);
-        const int c = kk * 2 + (lane >> 5);
-        return *reinterpret_cast<const bf16x8*>(lds_tile + r * (BK * 2) + ((c ^ swz_kc<BK>(r)) << 4));
-    } else {
-        // two transposing reads: each hands this lane 4 consecutive reduction elements of column
-        // row0 + (lane & 31); lane a of a 16-lane group addresses reduction row a/4, columns 4*(a%4)..+3
-        const int i = lane & 15;
-        const int krow = kk * 16 + ((lane >> 5) << 3) + (i >> 2);
-        const int n = row0 + (((lane >> 4) & 1) << 4) + ((i & 3) << 2);
-        const int c = n >> 3, h = (n >> 2) & 1;
-        const int sw = (i >> 2) << 2;  // == swz_mc(krow) and == swz_mc(krow + 4)
-        const char* p = lds_tile + krow * (ROWS * 2) + ((c ^ sw) << 4) + (h << 3);
-        typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * (ROWS * 2)));
-        union { struct { s16x4 a, b; } s; bf16x8 v; } u;
-        u.s.a = lo;
-        u.s.b = hi;
-        return u.v;
+// LDS byte addresses from which this lane reads its MFMA fragments of one operand in one stage.
+// KC: one address per reduction sub-step kk (the tile index adds 32 rows = 4096 bytes, folded
+// into the instruction offset).  MC: one address per MFMA tile (the sub-step adds 16 reduction
+// rows, folded into the instruction offset).
+template <int ROWS, int LAYOUT, int NT>
+struct FragAddr {
+    static constexpr int N = (LAYOUT == KC) ? 4 : NT;
+    uint32_t a[N];
+    __device__ __forceinline__ void init(int row0, int lane, uint32_t tile_base) {
+        if (LAYOUT == KC) {
+            const int r = row0 + (lane & 31);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const int c = kk * 2 + (lane >> 5);
+                a[kk] = tile_base + r * (TILE_BK * 2) + ((c ^ swz_kc(r)) << 4);
+            }
+        } else {
+            const int i = lane & 15;
+            const int krow = ((lane >> 5) << 3) + (i >> 2);
+            const int sw = (i >> 2) << 2;  // == swz_mc(krow + 16 kk) and == swz_mc(krow + 4 + 16 kk)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int n = row0 + t * 32 + (((lane >> 4) & 1) << 4) + ((i & 3) << 2);
+                const int c = n >> 3, h = (n >> 2) & 1;
+                a[t] = tile_base + krow * (ROWS * 2) + ((c ^ sw) << 4) + (h << 3);
+            }
+        }
     }
-}
+    // fragment of MFMA tile t at sub-step kk (both compile-time after unrolling)
+    __device__ __forceinline__ bf16x8 read(const char* lds0, int t, int kk) const {
+        if (LAYOUT == KC) {
+            return *reinterpret_cast<const bf16x8*>(lds0 + a[kk] + t * (32 * TILE_BK * 2));
+        } else {
+            // two transposing reads: each hands this lane 4 consecutive reduction elements of its column;
+            // lane i of a 16-lane group addresses reduction row i/4, columns 4*(i%4)..+3
+            typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+            const char* p = lds0 + a[t] + kk * (16 * ROWS * 2);
+            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
+            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * (ROWS * 2)));
+            union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+            u.s.a = lo;
+            u.s.b = hi;
+            return u.v;
+        }
+    }
+};
 
-// Tells the scheduler to deal the memory instructions of a half-iteration out between its MFMAs:
-// one MFMA occupies the matrix pipe for 32 cycles, the wave can issue loads and LDS reads in
-// that shadow, and the other wave of the SIMD fills the pipe meanwhile.
+// Tells the scheduler to deal the memory instructions of a group out between its MFMAs: one MFMA
+// occupies the matrix pipe for 32 cycles, the wave can issue loads and LDS reads in that shadow,
+// and the other wave of the SIMD fills the pipe meanwhile.
 template <int N_MFMA, int N_VMEM, int N_DS, int I>
 struct Interleave {
     static __device__ __forceinline__ void run() {
@@ -170,23 +204,34 @@ struct Interleave {
 #define AXO_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
 // One BM x BN output tile with its top-left corner at (i0, j0), whole reduction.
-template <int BM, int BN, int WGM, int WGN, int LA, int LB, int BK, int STAGES>
+template <int BM, int BN, int WGM, int WGN, int LA, int LB>
 __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, const int j0, char* smem) {
-    using C = TileCfg<BM, BN, WGM, WGN, BK, STAGES>;
-    constexpr int KK = BK / 16;  // MFMA sub-steps per stage
+    using C = TileCfg<BM, BN, WGM, WGN>;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
-    const int KT = g.R / BK;
-    const int64_t a_step = (LA == KC) ? BK : (int64_t)BK * g.lda;
-    const int64_t b_step = (LB == KC) ? BK : (int64_t)BK * g.ldb;
+    const int KT = g.R / TILE_BK;
+
+    // global side: descriptor at the tile origin, per-lane offsets, scalar step
     const bf16_t* Ab = (LA == KC) ? g.A + (int64_t)i0 * g.lda : g.A + i0;
     const bf16_t* Bb = (LB == KC) ? g.B + (int64_t)j0 * g.ldb : g.B + j0;
+    const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Ab), 0, 0xFFFFFFFFu, 0x00020000);
+    const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Bb), 0, 0xFFFFFFFFu, 0x00020000);
+    const uint32_t a_step = (uint32_t)((LA == KC) ? TILE_BK * 2 : (int64_t)TILE_BK * g.lda * 2);
+    const uint32_t b_step = (uint32_t)((LB == KC) ? TILE_BK * 2 : (int64_t)TILE_BK * g.ldb * 2);
+    uint32_t a_off[C::A_ROUNDS], b_off[C::B_ROUNDS];
+    load_offsets<BM, LA, C::A_ROUNDS>(tid, g.lda, a_off);
+    load_offsets<BN, LB, C::B_ROUNDS>(tid, g.ldb, b_off);
 
-    int64_t a_off[C::A_ROUNDS], b_off[C::B_ROUNDS];
-    load_offsets<BM, LA, BK, C::A_ROUNDS>(tid, g.lda, a_off);
-    load_offsets<BN, LB, BK, C::B_ROUNDS>(tid, g.ldb, b_off);
+    // LDS side: fragment addresses for both stages
+    FragAddr<BM, LA, C::TM> fra[2];
+    FragAddr<BN, LB, C::TN> frb[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        fra[s].init(wm * C::WTM, lane, s * C::STAGE_BYTES);
+        frb[s].init(wn * C::WTN, lane, s * C::STAGE_BYTES + C::A_BYTES);
+    }
 
     f32x16 acc[C::TM][C::TN];
 #pragma unroll
@@ -197,79 +242,82 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
             for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
 
     bf16x8 fa[2][C::TM], fb[2][C::TN];
-    auto read_frags = [&](int buf, const char* stage, int kk) {
+    // fragments are requested in the order the MFMAs below consume them (all B tiles are needed
+    // within the first TN MFMAs, the A tiles one after the other)
+    auto read_frags = [&](int set, int s, int kk) __attribute__((always_inline)) {
+        fb[set][0] = frb[s].read(smem, 0, kk);
+        fa[set][0] = fra[s].read(smem, 0, kk);
 #pragma unroll
-        for (int a = 0; a < C::TM; ++a) fa[buf][a] = read_fragment<BM, LA, BK>(stage, wm * C::WTM + a * 32, kk, lane);
+        for (int b = 1; b < C::TN; ++b) fb[set][b] = frb[s].read(smem, b, kk);
 #pragma unroll
-        for (int b = 0; b < C::TN; ++b) fb[buf][b] = read_fragment<BN, LB, BK>(stage + C::A_BYTES, wn * C::WTN + b * 32, kk, lane);
+        for (int a = 1; a < C::TM; ++a) fa[set][a] = fra[s].read(smem, a, kk);
     };
-    auto mfma_group = [&](int buf) {
+    auto mfma_group = [&](int set) __attribute__((always_inline)) {
 #pragma unroll
         for (int a = 0; a < C::TM; ++a)
 #pragma unroll
             for (int b = 0; b < C::TN; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][b], fa[buf][a], acc[a][b], 0, 0, 0);
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][b], fa[set][a], acc[a][b], 0, 0, 0);
     };
     constexpr int N_MFMA = C::TM * C::TN;
     constexpr int N_DSREAD = (LA == KC ? 1 : 2) * C::TM + (LB == KC ? 1 : 2) * C::TN;
-    auto issue_stage = [&](int step) {
-        char* dst = smem + (step % STAGES) * C::STAGE_BYTES;
-        issue_loads<C::A_ROUNDS>(Ab + step * a_step, a_off, dst, wave);
-        issue_loads<C::B_ROUNDS>(Bb + step * b_step, b_off, dst + C::A_BYTES, wave);
+    uint32_t a_soff = 0, b_soff = 0;  // scalar byte offsets of the reduction step being loaded
+    constexpr int NL = C::LOADS_PER_STAGE;
+    auto issue_stage = [&](int s) __attribute__((always_inline)) {
+        char* dst = smem + s * C::STAGE_BYTES;
+        issue_loads<C::A_ROUNDS>(a_rsrc, a_off, a_soff, dst, wave);
+        issue_loads<C::B_ROUNDS>(b_rsrc, b_off, b_soff, dst + C::A_BYTES, wave);
+        a_soff += a_step;
+        b_soff += b_step;
     };
-    auto interleave = [&](auto n_vmem, auto n_ds) { Interleave<N_MFMA, decltype(n_vmem)::value, decltype(n_ds)::value, 0>::run(); };
-    using IC0 = std::integral_constant<int, 0>;
-    using ICD = std::integral_constant<int, N_DSREAD>;
-    using ICV = std::integral_constant<int, C::LOADS_PER_STAGE>;
 
-    // Ring schedule.  Step s lives in slot s % STAGES.  Before the loop steps 0..STAGES-1 are
-    // issued.  Iteration j: read the second half of step j's fragments while the MFMAs of its
-    // first half run; then wait until this wave's copy of step j+1 has landed (all but the
-    // youngest STAGES-2 steps), workgroup barrier (everyone's copy landed, everyone is done with
-    // slot j), refill slot j with step j+STAGES, read the first fragments of step j+1 while the
-    // MFMAs of step j's second half run.  A step is issued STAGES-1 iterations before it is read.
-    // The steady-state loop is branch free so that the compiler can interleave across it; the
-    // last STAGES iterations (nothing left to issue) run in a second loop.
-    if (KT > 0) {
-        const int pre = KT < STAGES ? KT : STAGES;
-        for (int s = 0; s < pre; ++s) issue_stage(s);
-        if (pre == STAGES) AXO_WAIT_VMCNT(C::LOADS_PER_STAGE * (STAGES - 1));
-        else AXO_WAIT_VMCNT(0);
+    // One reduction step held in stage s (compile-time).  On entry the fragments of sub-step 0
+    // are in register set 0.  The workgroup barrier sits before the last MFMA group: at that
+    // point this wave has read all its fragments of stage s and has seen its own copies of stage
+    // s^1 land, so after the barrier stage s can be refilled (step j+2) and stage s^1 read; both
+    // are issued in the shadow of the last MFMA group.
+    // Wave priorities fall through the step and are highest right after the barrier: of the two
+    // waves of a SIMD the one that lags is then preferred by the MFMA arbiter, which keeps them
+    // from serialising (measured: without this one wave of each SIMD waits at the barrier for
+    // about 40 % of the step while the other one is starved of MFMA issue slots).
+    auto step = [&](auto s_tag, const bool load, const bool next) __attribute__((always_inline)) {
+        constexpr int s = decltype(s_tag)::value;
+        AXO_SETPRIO(2);
+        read_frags(1, s, 1);
+        mfma_group(0);
+        Interleave<N_MFMA, 0, N_DSREAD, 0>::run();
+        AXO_SETPRIO(1);
+        read_frags(0, s, 2);
+        mfma_group(1);
+        Interleave<N_MFMA, 0, N_DSREAD, 0>::run();
+        AXO_SETPRIO(0);
+        read_frags(1, s, 3);
+        mfma_group(0);
+        Interleave<N_MFMA, 0, N_DSREAD, 0>::run();
+        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
         __syncthreads();
-        read_frags(0, smem, 0);
+        AXO_SETPRIO(3);
+        if (load) issue_stage(s);
+        if (next) read_frags(0, s ^ 1, 0);
+        mfma_group(1);
+        Interleave<N_MFMA, NL, N_DSREAD, 0>::run();
+    };
+    using T0 = std::integral_constant<int, 0>;
+    using T1 = std::integral_constant<int, 1>;
+
+    // KT is even and at least 2 (the host only sends reductions that are multiples of 128 here)
+    issue_stage(0);
+    issue_stage(1);
+    AXO_WAIT_VMCNT(C::LOADS_PER_STAGE);  // step 0 has landed, step 1 may be in flight
+    __syncthreads();
+    read_frags(0, 0, 0);
+    for (int j = 0; j + 2 < KT; j += 2) {  // steady state, branch free: steps j, j+1; refills j+2, j+3
+        step(T0{}, true, true);
+        step(T1{}, true, true);
     }
-    int j = 0;
-    for (; j + STAGES < KT; ++j) {
-        const char* cur = smem + (j % STAGES) * C::STAGE_BYTES;
-#pragma unroll
-        for (int kk = 0; kk + 1 < KK; ++kk) {
-            read_frags((kk + 1) & 1, cur, kk + 1);
-            mfma_group(kk & 1);
-            interleave(IC0{}, ICD{});
-        }
-        AXO_WAIT_VMCNT(C::LOADS_PER_STAGE * (STAGES - 2));
-        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wave's reads of slot j are done
-        __syncthreads();
-        issue_stage(j + STAGES);
-        read_frags(0, smem + ((j + 1) % STAGES) * C::STAGE_BYTES, 0);
-        mfma_group((KK - 1) & 1);
-        interleave(ICV{}, ICD{});
-    }
-    for (; j < KT; ++j) {
-        const char* cur = smem + (j % STAGES) * C::STAGE_BYTES;
-#pragma unroll
-        for (int kk = 0; kk + 1 < KK; ++kk) {
-            read_frags((kk + 1) & 1, cur, kk + 1);
-            mfma_group(kk & 1);
-            interleave(IC0{}, ICD{});
-        }
-        AXO_WAIT_VMCNT(0);  // fewer than STAGES-2 steps are outstanding now: wait for all of them
-        __builtin_amdgcn_s_waitcnt(0xC07F);
-        __syncthreads();
-        if (j + 1 < KT) read_frags(0, smem + ((j + 1) % STAGES) * C::STAGE_BYTES, 0);
-        mfma_group((KK - 1) & 1);
-        interleave(IC0{}, ICD{});
-    }
+    step(T0{}, false, true);  // the last two steps: nothing left to load
+    step(T1{}, false, false);
+    AXO_SETPRIO(0);
 
     // ---- epilogue: acc[a][b][e] is C[i0 + wm*WTM + a*32 + (lane&31)][j0 + wn*WTN + b*32 + 8*(e/4) + 4*(lane/32) + e%4]
     __syncthreads();  // all waves are done reading the operand buffers
@@ -319,9 +367,8 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     }
 }
 
-constexpr int MIX_BK = 64, MIX_STAGES = 2;
-using MixBigCfg = TileCfg<256, 256, 2, 4, MIX_BK, MIX_STAGES>;
-using MixSmallCfg = TileCfg<256, 128, 4, 2, MIX_BK, MIX_STAGES>;
+using MixBigCfg = TileCfg<256, 256, 2, 4>;
+using MixSmallCfg = TileCfg<256, 128, 4, 2>;
 constexpr int MIX_LDS_BYTES = MixBigCfg::LDS_BYTES > MixSmallCfg::LDS_BYTES ? MixBigCfg::LDS_BYTES : MixSmallCfg::LDS_BYTES;
 
 // One launch over both regions of a TileSched.
@@ -332,11 +379,11 @@ __global__ void __launch_bounds__(TILE_THREADS, 1) gemm_mixed_kernel(GemmArgs g,
     int tm, tn;
     if (bid < sc.n_big) {
         tile_of_index(xcd_contiguous(bid, sc.n_big), sc.tiles_m, sc.big_cols, sc.group_m, tm, tn);
-        gemm_tile_body<256, 256, 2, 4, LA, LB, MIX_BK, MIX_STAGES>(g, tm * 256, tn * 256, smem);
+        gemm_tile_body<256, 256, 2, 4, LA, LB>(g, tm * 256, tn * 256, smem);
     } else {
         const int n_small = (int)gridDim.x - sc.n_big;
         tile_of_index(xcd_contiguous(bid - sc.n_big, n_small), sc.tiles_m, sc.small_cols, sc.group_m, tm, tn);
-        gemm_tile_body<256, 128, 4, 2, LA, LB, MIX_BK, MIX_STAGES>(g, tm * 256, sc.big_cols * 256 + tn * 128, smem);
+        gemm_tile_body<256, 128, 4, 2, LA, LB>(g, tm * 256, sc.big_cols * 256 + tn * 128, smem);
     }
 }
 
