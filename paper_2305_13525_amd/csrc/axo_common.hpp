@@ -48,6 +48,17 @@ __device__ __forceinline__ bf16_t f32_to_bf16_bits(float f) {
     return (bf16_t)(u >> 16);
 }
 
+// Two fp32 values -> packed bf16 pair (low half = a), round to nearest even, NaN stays NaN: the
+// gfx950 packed conversion instruction.
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    const f32x2 v = {a, b};
+    const bf16x2 r = __builtin_convertvector(v, bf16x2);
+    union { bf16x2 v; uint32_t u; } u;
+    u.v = r;
+    return u.u;
+}
+
 // GELU, tanh form: 0.5 v (1 + tanh(z)) = v * sigmoid(2 z), z = sqrt(2/pi) (v + 0.044715 v^3).
 // The sigmoid form has no cancellation for large negative v.
 __device__ __forceinline__ float gelu_tanh(float v) {

@@ -322,35 +322,46 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     // ---- epilogue: acc[a][b][e] is C[i0 + wm*WTM + a*32 + (lane&31)][j0 + wn*WTN + b*32 + 8*(e/4) + 4*(lane/32) + e%4]
     __syncthreads();  // all waves are done reading the operand buffers
     char* stage = smem + wave * (C::WTM * C::EPI_STRIDE);
-    const int epi = g.epilogue;
+    // the epilogue kind is decided once, outside the element loops: the plain path is then
+    // straight-line code (the activation code is large; branching around it per element made the
+    // epilogue several times slower than the stores it feeds)
+    auto convert_and_stage = [&](auto epi_tag) __attribute__((always_inline)) {
+        constexpr int EPI = decltype(epi_tag)::value;
 #pragma unroll
-    for (int b = 0; b < C::TN; ++b) {
+        for (int b = 0; b < C::TN; ++b) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int ncol = b * 32 + 8 * q + 4 * (lane >> 5);  // within the wave tile
-            float bv[4] = {0.f, 0.f, 0.f, 0.f};
-            if (epi != EPI_NONE && g.add_bias) {
-                const uint2 raw = *reinterpret_cast<const uint2*>(g.bias + j0 + wn * C::WTN + ncol);
-                bv[0] = __uint_as_float(raw.x << 16);
-                bv[1] = __uint_as_float(raw.x & 0xFFFF0000u);
-                bv[2] = __uint_as_float(raw.y << 16);
-                bv[3] = __uint_as_float(raw.y & 0xFFFF0000u);
-            }
-#pragma unroll
-            for (int a = 0; a < C::TM; ++a) {
-                float v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    v[e] = acc[a][b][q * 4 + e];
-                    if (epi != EPI_NONE) v[e] = apply_epilogue(v[e], bv[e], epi);
+            for (int q = 0; q < 4; ++q) {
+                const int ncol = b * 32 + 8 * q + 4 * (lane >> 5);  // within the wave tile
+                float bv[4] = {0.f, 0.f, 0.f, 0.f};
+                if (EPI != EPI_NONE && g.add_bias) {
+                    const uint2 raw = *reinterpret_cast<const uint2*>(g.bias + j0 + wn * C::WTN + ncol);
+                    bv[0] = __uint_as_float(raw.x << 16);
+                    bv[1] = __uint_as_float(raw.x & 0xFFFF0000u);
+                    bv[2] = __uint_as_float(raw.y << 16);
+                    bv[3] = __uint_as_float(raw.y & 0xFFFF0000u);
                 }
-                uint2 packed;
-                packed.x = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
-                packed.y = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
-                const int mrow = a * 32 + (lane & 31);
-                *reinterpret_cast<uint2*>(stage + mrow * C::EPI_STRIDE + ncol * 2) = packed;
+#pragma unroll
+                for (int a = 0; a < C::TM; ++a) {
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = acc[a][b][q * 4 + e];
+                        if (EPI != EPI_NONE) v[e] = apply_epilogue(v[e], bv[e], EPI);
+                    }
+                    uint2 packed;
+                    packed.x = pack_bf16x2(v[0], v[1]);
+                    packed.y = pack_bf16x2(v[2], v[3]);
+                    const int mrow = a * 32 + (lane & 31);
+                    *reinterpret_cast<uint2*>(stage + mrow * C::EPI_STRIDE + ncol * 2) = packed;
+                }
             }
         }
+    };
+    switch (g.epilogue) {
+        case EPI_NONE: convert_and_stage(std::integral_constant<int, EPI_NONE>{}); break;
+        case EPI_BIAS: convert_and_stage(std::integral_constant<int, EPI_BIAS>{}); break;
+        case EPI_BIAS_GELU_TANH: convert_and_stage(std::integral_constant<int, EPI_BIAS_GELU_TANH>{}); break;
+        default: convert_and_stage(std::integral_constant<int, EPI_BIAS_GELU_ERF>{}); break;
     }
     // the staging region is private to the wave: only wave-level ordering is needed
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
