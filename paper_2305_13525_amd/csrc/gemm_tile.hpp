@@ -5,7 +5,7 @@
 //
 // One 512-thread workgroup (8 waves, two per SIMD) owns a BM x BN output tile and walks the
 // reduction in steps of 64 through two LDS stages.  Operand tiles are copied global -> LDS by
-// direct-to-LDS buffer loads (16 bytes per lane, no register staging).  MFMA 32x32x16 fragments
+// direct-to-LDS buffer loads (16 bytes per lane, no register staging).  MFMA 16x16x32 fragments
 // are read from LDS with ds_read_b128 when the reduction index is contiguous in memory (KC) and
 // with the transposing ds_read_b64_tr_b16 when the output index is contiguous (MC), so no operand
 // is ever transposed in global memory.  16-byte chunks are permuted on their way into LDS (the
@@ -19,8 +19,10 @@
 // immediate offset; the loop is unrolled over the two stages so that nothing depends on the
 // stage index at run time.
 //
-// The accumulators hold the transposed 32x32 tile (B fragment first), which gives each lane 4
-// consecutive output columns; the epilogue rounds to bf16 once, stages the wave's sub-tile through
+// The 16x16x32 MFMA is used rather than the 32x32x16 one: at the chip's power limit a loop of
+// nothing but MFMAs on random operands sustains 2.0 PFLOP/s with the former and 1.75 with the
+// latter (two waves per SIMD).  The accumulators hold the transposed 16x16 tile (B fragment
+// first), which gives each lane 4 consecutive output columns; the epilogue rounds to bf16 once, stages the wave's sub-tile through
 // LDS and writes full 128-byte row segments.
 #pragma once
 #include <type_traits>
@@ -51,7 +53,9 @@ typedef __attribute__((address_space(3))) void* lds_void_ptr;
 // 16 consecutive rows read at the same c then hit 16 different 16-byte bank groups.
 __device__ __forceinline__ int swz_kc(int r) { return (r >> 1) & 7; }
 // MC tile in LDS: reduction row k is ROWS*2 bytes, chunk c stored at c ^ 4*(k % 4): the four
-// reduction rows one transposing read touches land in different bank groups.
+// reduction rows one 16-lane group touches in a transposing read land in different bank groups,
+// and chunk bit 1 (which of two neighbouring 16-wide tiles) is left alone so that both tiles can
+// be addressed from one register.
 __device__ __forceinline__ int swz_mc(int k) { return (k & 3) << 2; }
 
 // How one launch is cut into workgroups.  The output is covered by two column regions: columns
@@ -90,7 +94,8 @@ __device__ __forceinline__ void tile_of_index(int t, int tiles_m, int tiles_n, i
 template <int BM, int BN, int WGM, int WGN>
 struct TileCfg {
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
-    static constexpr int TM = WTM / 32, TN = WTN / 32;    // MFMA tiles per wave
+    static constexpr int TM = WTM / 16, TN = WTN / 16;    // 16x16 MFMA tiles per wave
+    static constexpr int AH = TM / 2;                     // A tiles per MFMA group (half the wave tile's rows)
     static constexpr int A_BYTES = BM * TILE_BK * 2, B_BYTES = BN * TILE_BK * 2;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int A_ROUNDS = BM * (TILE_BK / 8) / TILE_THREADS, B_ROUNDS = BN * (TILE_BK / 8) / TILE_THREADS;
@@ -100,7 +105,7 @@ struct TileCfg {
     static constexpr int RING_BYTES = 2 * STAGE_BYTES;
     static constexpr int LDS_BYTES = (RING_BYTES > EPI_BYTES) ? RING_BYTES : EPI_BYTES;
     static_assert(WGM * WGN == 8, "8 waves");
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 MFMA tiles");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of pairs of 16x16 MFMA tiles");
     static_assert((BM * (TILE_BK / 8)) % TILE_THREADS == 0 && (BN * (TILE_BK / 8)) % TILE_THREADS == 0, "whole load rounds");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
 };
@@ -137,42 +142,44 @@ __device__ __forceinline__ void issue_loads(__amdgpu_buffer_rsrc_t rsrc, const u
 }
 
 // LDS byte addresses from which this lane reads its MFMA fragments of one operand in one stage.
-// KC: one address per reduction sub-step kk (the tile index adds 32 rows = 4096 bytes, folded
-// into the instruction offset).  MC: one address per MFMA tile (the sub-step adds 16 reduction
-// rows, folded into the instruction offset).
+// A 16x16x32 fragment is 8 consecutive reduction elements (lane/16 selects which 8 of the 32) of
+// row/column lane%16 of the tile.  KC: one address per 32-wide reduction sub-step (the tile
+// index adds 16 rows = 2048 bytes, folded into the instruction offset).  MC: one address per
+// pair of neighbouring MFMA tiles (the second tile adds 32 bytes, the sub-step 32 reduction rows,
+// both folded into the instruction offset).
 template <int ROWS, int LAYOUT, int NT>
 struct FragAddr {
-    static constexpr int N = (LAYOUT == KC) ? 4 : NT;
+    static constexpr int N = (LAYOUT == KC) ? 2 : NT / 2;
     uint32_t a[N];
     __device__ __forceinline__ void init(int row0, int lane, uint32_t tile_base) {
         if (LAYOUT == KC) {
-            const int r = row0 + (lane & 31);
+            const int r = row0 + (lane & 15);
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const int c = kk * 2 + (lane >> 5);
-                a[kk] = tile_base + r * (TILE_BK * 2) + ((c ^ swz_kc(r)) << 4);
+            for (int kq = 0; kq < 2; ++kq) {
+                const int c = kq * 4 + (lane >> 4);
+                a[kq] = tile_base + r * (TILE_BK * 2) + ((c ^ swz_kc(r)) << 4);
             }
         } else {
             const int i = lane & 15;
-            const int krow = ((lane >> 5) << 3) + (i >> 2);
-            const int sw = (i >> 2) << 2;  // == swz_mc(krow + 16 kk) and == swz_mc(krow + 4 + 16 kk)
+            const int krow = ((lane >> 4) << 3) + (i >> 2);
+            const int sw = swz_mc(krow);  // unchanged by the +4 and +32 row offsets added in read()
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const int n = row0 + t * 32 + (((lane >> 4) & 1) << 4) + ((i & 3) << 2);
+            for (int t = 0; t < NT / 2; ++t) {
+                const int n = row0 + t * 32 + ((i & 3) << 2);
                 const int c = n >> 3, h = (n >> 2) & 1;
                 a[t] = tile_base + krow * (ROWS * 2) + ((c ^ sw) << 4) + (h << 3);
             }
         }
     }
-    // fragment of MFMA tile t at sub-step kk (both compile-time after unrolling)
-    __device__ __forceinline__ bf16x8 read(const char* lds0, int t, int kk) const {
+    // fragment of MFMA tile t at 32-wide sub-step kq (both compile-time after unrolling)
+    __device__ __forceinline__ bf16x8 read(const char* lds0, int t, int kq) const {
         if (LAYOUT == KC) {
-            return *reinterpret_cast<const bf16x8*>(lds0 + a[kk] + t * (32 * TILE_BK * 2));
+            return *reinterpret_cast<const bf16x8*>(lds0 + a[kq] + t * (16 * TILE_BK * 2));
         } else {
             // two transposing reads: each hands this lane 4 consecutive reduction elements of its column;
             // lane i of a 16-lane group addresses reduction row i/4, columns 4*(i%4)..+3
             typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
-            const char* p = lds0 + a[t] + kk * (16 * ROWS * 2);
+            const char* p = lds0 + a[t >> 1] + (t & 1) * 32 + kq * (32 * ROWS * 2);
             s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
             s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * (ROWS * 2)));
             union { struct { s16x4 a, b; } s; bf16x8 v; } u;
@@ -233,34 +240,36 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
         frb[s].init(wn * C::WTN, lane, s * C::STAGE_BYTES + C::A_BYTES);
     }
 
-    f32x16 acc[C::TM][C::TN];
+    f32x4 acc[C::TM][C::TN];
 #pragma unroll
     for (int a = 0; a < C::TM; ++a)
 #pragma unroll
         for (int b = 0; b < C::TN; ++b)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
+            for (int e = 0; e < 4; ++e) acc[a][b][e] = 0.0f;
 
-    bf16x8 fa[2][C::TM], fb[2][C::TN];
-    // fragments are requested in the order the MFMAs below consume them (all B tiles are needed
-    // within the first TN MFMAs, the A tiles one after the other)
-    auto read_frags = [&](int set, int s, int kk) __attribute__((always_inline)) {
-        fb[set][0] = frb[s].read(smem, 0, kk);
-        fa[set][0] = fra[s].read(smem, 0, kk);
+    // A reduction step of 64 is four MFMA groups: (sub-step kq, row half ah) for kq, ah in {0, 1};
+    // a group multiplies AH A fragments with all TN B fragments of its sub-step.  A fragments are
+    // double buffered per group, B fragments per sub-step.
+    bf16x8 fa[2][C::AH], fb[2][C::TN];
+    auto read_a = [&](int set, int s, int kq, int ah) __attribute__((always_inline)) {
 #pragma unroll
-        for (int b = 1; b < C::TN; ++b) fb[set][b] = frb[s].read(smem, b, kk);
-#pragma unroll
-        for (int a = 1; a < C::TM; ++a) fa[set][a] = fra[s].read(smem, a, kk);
+        for (int a = 0; a < C::AH; ++a) fa[set][a] = fra[s].read(smem, ah * C::AH + a, kq);
     };
-    auto mfma_group = [&](int set) __attribute__((always_inline)) {
+    auto read_b = [&](int set, int s, int kq) __attribute__((always_inline)) {
 #pragma unroll
-        for (int a = 0; a < C::TM; ++a)
+        for (int b = 0; b < C::TN; ++b) fb[set][b] = frb[s].read(smem, b, kq);
+    };
+    auto mfma_group = [&](int aset, int bset, int ah) __attribute__((always_inline)) {
+#pragma unroll
+        for (int a = 0; a < C::AH; ++a)
 #pragma unroll
             for (int b = 0; b < C::TN; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][b], fa[set][a], acc[a][b], 0, 0, 0);
+                acc[ah * C::AH + a][b] =
+                    __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[bset][b], fa[aset][a], acc[ah * C::AH + a][b], 0, 0, 0);
     };
-    constexpr int N_MFMA = C::TM * C::TN;
-    constexpr int N_DSREAD = (LA == KC ? 1 : 2) * C::TM + (LB == KC ? 1 : 2) * C::TN;
+    constexpr int N_MFMA = C::AH * C::TN;
+    constexpr int RD_A = (LA == KC ? 1 : 2) * C::AH, RD_B = (LB == KC ? 1 : 2) * C::TN;
     uint32_t a_soff = 0, b_soff = 0;  // scalar byte offsets of the reduction step being loaded
     constexpr int NL = C::LOADS_PER_STAGE;
     auto issue_stage = [&](int s) __attribute__((always_inline)) {
@@ -283,24 +292,28 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     auto step = [&](auto s_tag, const bool load, const bool next) __attribute__((always_inline)) {
         constexpr int s = decltype(s_tag)::value;
         AXO_SETPRIO(2);
-        read_frags(1, s, 1);
-        mfma_group(0);
-        Interleave<N_MFMA, 0, N_DSREAD, 0>::run();
+        read_a(1, s, 0, 1);
+        mfma_group(0, 0, 0);  // (kq 0, ah 0)
+        Interleave<N_MFMA, 0, RD_A, 0>::run();
         AXO_SETPRIO(1);
-        read_frags(0, s, 2);
-        mfma_group(1);
-        Interleave<N_MFMA, 0, N_DSREAD, 0>::run();
+        read_a(0, s, 1, 0);
+        read_b(1, s, 1);
+        mfma_group(1, 0, 1);  // (kq 0, ah 1)
+        Interleave<N_MFMA, 0, RD_A + RD_B, 0>::run();
         AXO_SETPRIO(0);
-        read_frags(1, s, 3);
-        mfma_group(0);
-        Interleave<N_MFMA, 0, N_DSREAD, 0>::run();
+        read_a(1, s, 1, 1);
+        mfma_group(0, 1, 0);  // (kq 1, ah 0)
+        Interleave<N_MFMA, 0, RD_A, 0>::run();
         __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
         __syncthreads();
         AXO_SETPRIO(3);
         if (load) issue_stage(s);
-        if (next) read_frags(0, s ^ 1, 0);
-        mfma_group(1);
-        Interleave<N_MFMA, NL, N_DSREAD, 0>::run();
+        if (next) {
+            read_a(0, s ^ 1, 0, 0);
+            read_b(0, s ^ 1, 0);
+        }
+        mfma_group(1, 1, 1);  // (kq 1, ah 1)
+        Interleave<N_MFMA, NL, RD_A + RD_B, 0>::run();
     };
     using T0 = std::integral_constant<int, 0>;
     using T1 = std::integral_constant<int, 1>;
@@ -310,7 +323,8 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     issue_stage(1);
     AXO_WAIT_VMCNT(C::LOADS_PER_STAGE);  // step 0 has landed, step 1 may be in flight
     __syncthreads();
-    read_frags(0, 0, 0);
+    read_a(0, 0, 0, 0);
+    read_b(0, 0, 0);
     for (int j = 0; j + 2 < KT; j += 2) {  // steady state, branch free: steps j, j+1; refills j+2, j+3
         step(T0{}, true, true);
         step(T1{}, true, true);
@@ -319,7 +333,7 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     step(T1{}, false, false);
     AXO_SETPRIO(0);
 
-    // ---- epilogue: acc[a][b][e] is C[i0 + wm*WTM + a*32 + (lane&31)][j0 + wn*WTN + b*32 + 8*(e/4) + 4*(lane/32) + e%4]
+    // ---- epilogue: acc[a][b][e] is C[i0 + wm*WTM + a*16 + lane%16][j0 + wn*WTN + b*16 + 4*(lane/16) + e]
     __syncthreads();  // all waves are done reading the operand buffers
     char* stage = smem + wave * (C::WTM * C::EPI_STRIDE);
     // the epilogue kind is decided once, outside the element loops: the plain path is then
@@ -329,31 +343,28 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
         constexpr int EPI = decltype(epi_tag)::value;
 #pragma unroll
         for (int b = 0; b < C::TN; ++b) {
+            const int ncol = b * 16 + 4 * (lane >> 4);  // within the wave tile
+            float bv[4] = {0.f, 0.f, 0.f, 0.f};
+            if (EPI != EPI_NONE && g.add_bias) {
+                const uint2 raw = *reinterpret_cast<const uint2*>(g.bias + j0 + wn * C::WTN + ncol);
+                bv[0] = __uint_as_float(raw.x << 16);
+                bv[1] = __uint_as_float(raw.x & 0xFFFF0000u);
+                bv[2] = __uint_as_float(raw.y << 16);
+                bv[3] = __uint_as_float(raw.y & 0xFFFF0000u);
+            }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int ncol = b * 32 + 8 * q + 4 * (lane >> 5);  // within the wave tile
-                float bv[4] = {0.f, 0.f, 0.f, 0.f};
-                if (EPI != EPI_NONE && g.add_bias) {
-                    const uint2 raw = *reinterpret_cast<const uint2*>(g.bias + j0 + wn * C::WTN + ncol);
-                    bv[0] = __uint_as_float(raw.x << 16);
-                    bv[1] = __uint_as_float(raw.x & 0xFFFF0000u);
-                    bv[2] = __uint_as_float(raw.y << 16);
-                    bv[3] = __uint_as_float(raw.y & 0xFFFF0000u);
+            for (int a = 0; a < C::TM; ++a) {
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[e] = acc[a][b][e];
+                    if (EPI != EPI_NONE) v[e] = apply_epilogue(v[e], bv[e], EPI);
                 }
-#pragma unroll
-                for (int a = 0; a < C::TM; ++a) {
-                    float v[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        v[e] = acc[a][b][q * 4 + e];
-                        if (EPI != EPI_NONE) v[e] = apply_epilogue(v[e], bv[e], EPI);
-                    }
-                    uint2 packed;
-                    packed.x = pack_bf16x2(v[0], v[1]);
-                    packed.y = pack_bf16x2(v[2], v[3]);
-                    const int mrow = a * 32 + (lane & 31);
-                    *reinterpret_cast<uint2*>(stage + mrow * C::EPI_STRIDE + ncol * 2) = packed;
-                }
+                uint2 packed;
+                packed.x = pack_bf16x2(v[0], v[1]);
+                packed.y = pack_bf16x2(v[2], v[3]);
+                const int mrow = a * 16 + (lane & 15);
+                *reinterpret_cast<uint2*>(stage + mrow * C::EPI_STRIDE + ncol * 2) = packed;
             }
         }
     };
