@@ -52,11 +52,11 @@ typedef __attribute__((address_space(3))) void* lds_void_ptr;
 // KC tile in LDS: row r is 128 bytes = 8 chunks of 16 bytes, chunk c stored at c ^ ((r / 2) % 8):
 // 16 consecutive rows read at the same c then hit 16 different 16-byte bank groups.
 __device__ __forceinline__ int swz_kc(int r) { return (r >> 1) & 7; }
-// MC tile in LDS: reduction row k is ROWS*2 bytes, chunk c stored at c ^ 4*(k % 4): the four
-// reduction rows one 16-lane group touches in a transposing read land in different bank groups,
-// and chunk bit 1 (which of two neighbouring 16-wide tiles) is left alone so that both tiles can
-// be addressed from one register.
-__device__ __forceinline__ int swz_mc(int k) { return (k & 3) << 2; }
+// MC tile in LDS: reduction row k is ROWS*2 bytes, chunk c stored at c ^ f(k) with
+// f(k) = 4*(k % 4) + 2*((k / 8) % 2): half a wave's transposing read touches 8 reduction rows
+// (k % 4 and (k / 8) % 2 vary) times two 16-byte chunks, which then land in 16 different bank
+// groups (without the second term the 16-lane groups collide: measured 50 % conflict cycles).
+__device__ __forceinline__ int swz_mc(int k) { return ((k & 3) << 2) | (((k >> 3) & 1) << 1); }
 
 // How one launch is cut into workgroups.  The output is covered by two column regions: columns
 // [0, big_cols * 256) with 256x256 tiles and the rest with 256x128 tiles.  Workgroups
@@ -145,11 +145,13 @@ __device__ __forceinline__ void issue_loads(__amdgpu_buffer_rsrc_t rsrc, const u
 // A 16x16x32 fragment is 8 consecutive reduction elements (lane/16 selects which 8 of the 32) of
 // row/column lane%16 of the tile.  KC: one address per 32-wide reduction sub-step (the tile
 // index adds 16 rows = 2048 bytes, folded into the instruction offset).  MC: one address per
-// pair of neighbouring MFMA tiles (the second tile adds 32 bytes, the sub-step 32 reduction rows,
-// both folded into the instruction offset).
+// MFMA tile (the sub-step adds 32 reduction rows, folded into the instruction offset).  The two
+// stages of an operand are adjacent in LDS, so the stage is an instruction offset as well and one
+// set of addresses serves both.
 template <int ROWS, int LAYOUT, int NT>
 struct FragAddr {
-    static constexpr int N = (LAYOUT == KC) ? 2 : NT / 2;
+    static constexpr int N = (LAYOUT == KC) ? 2 : NT;
+    static constexpr int STAGE_STRIDE = ROWS * TILE_BK * 2;  // bytes between the operand's two stages
     uint32_t a[N];
     __device__ __forceinline__ void init(int row0, int lane, uint32_t tile_base) {
         if (LAYOUT == KC) {
@@ -164,22 +166,22 @@ struct FragAddr {
             const int krow = ((lane >> 4) << 3) + (i >> 2);
             const int sw = swz_mc(krow);  // unchanged by the +4 and +32 row offsets added in read()
 #pragma unroll
-            for (int t = 0; t < NT / 2; ++t) {
-                const int n = row0 + t * 32 + ((i & 3) << 2);
+            for (int t = 0; t < NT; ++t) {
+                const int n = row0 + t * 16 + ((i & 3) << 2);
                 const int c = n >> 3, h = (n >> 2) & 1;
                 a[t] = tile_base + krow * (ROWS * 2) + ((c ^ sw) << 4) + (h << 3);
             }
         }
     }
-    // fragment of MFMA tile t at 32-wide sub-step kq (both compile-time after unrolling)
-    __device__ __forceinline__ bf16x8 read(const char* lds0, int t, int kq) const {
+    // fragment of MFMA tile t at 32-wide sub-step kq of stage s (all compile-time after unrolling)
+    __device__ __forceinline__ bf16x8 read(const char* lds0, int s, int t, int kq) const {
         if (LAYOUT == KC) {
-            return *reinterpret_cast<const bf16x8*>(lds0 + a[kq] + t * (16 * TILE_BK * 2));
+            return *reinterpret_cast<const bf16x8*>(lds0 + a[kq] + s * STAGE_STRIDE + t * (16 * TILE_BK * 2));
         } else {
             // two transposing reads: each hands this lane 4 consecutive reduction elements of its column;
             // lane i of a 16-lane group addresses reduction row i/4, columns 4*(i%4)..+3
             typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
-            const char* p = lds0 + a[t >> 1] + (t & 1) * 32 + kq * (32 * ROWS * 2);
+            const char* p = lds0 + a[t] + s * STAGE_STRIDE + kq * (32 * ROWS * 2);
             s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
             s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * (ROWS * 2)));
             union { struct { s16x4 a, b; } s; bf16x8 v; } u;
@@ -231,14 +233,11 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     load_offsets<BM, LA, C::A_ROUNDS>(tid, g.lda, a_off);
     load_offsets<BN, LB, C::B_ROUNDS>(tid, g.ldb, b_off);
 
-    // LDS side: fragment addresses for both stages
-    FragAddr<BM, LA, C::TM> fra[2];
-    FragAddr<BN, LB, C::TN> frb[2];
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        fra[s].init(wm * C::WTM, lane, s * C::STAGE_BYTES);
-        frb[s].init(wn * C::WTN, lane, s * C::STAGE_BYTES + C::A_BYTES);
-    }
+    // LDS side: [A stage 0][A stage 1][B stage 0][B stage 1]; fragment addresses of stage 0
+    FragAddr<BM, LA, C::TM> fra;
+    FragAddr<BN, LB, C::TN> frb;
+    fra.init(wm * C::WTM, lane, 0);
+    frb.init(wn * C::WTN, lane, 2 * C::A_BYTES);
 
     f32x4 acc[C::TM][C::TN];
 #pragma unroll
@@ -254,11 +253,11 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     bf16x8 fa[2][C::AH], fb[2][C::TN];
     auto read_a = [&](int set, int s, int kq, int ah) __attribute__((always_inline)) {
 #pragma unroll
-        for (int a = 0; a < C::AH; ++a) fa[set][a] = fra[s].read(smem, ah * C::AH + a, kq);
+        for (int a = 0; a < C::AH; ++a) fa[set][a] = fra.read(smem, s, ah * C::AH + a, kq);
     };
     auto read_b = [&](int set, int s, int kq) __attribute__((always_inline)) {
 #pragma unroll
-        for (int b = 0; b < C::TN; ++b) fb[set][b] = frb[s].read(smem, b, kq);
+        for (int b = 0; b < C::TN; ++b) fb[set][b] = frb.read(smem, s, b, kq);
     };
     auto mfma_group = [&](int aset, int bset, int ah) __attribute__((always_inline)) {
 #pragma unroll
@@ -273,9 +272,8 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     uint32_t a_soff = 0, b_soff = 0;  // scalar byte offsets of the reduction step being loaded
     constexpr int NL = C::LOADS_PER_STAGE;
     auto issue_stage = [&](int s) __attribute__((always_inline)) {
-        char* dst = smem + s * C::STAGE_BYTES;
-        issue_loads<C::A_ROUNDS>(a_rsrc, a_off, a_soff, dst, wave);
-        issue_loads<C::B_ROUNDS>(b_rsrc, b_off, b_soff, dst + C::A_BYTES, wave);
+        issue_loads<C::A_ROUNDS>(a_rsrc, a_off, a_soff, smem + s * C::A_BYTES, wave);
+        issue_loads<C::B_ROUNDS>(b_rsrc, b_off, b_soff, smem + 2 * C::A_BYTES + s * C::B_BYTES, wave);
         a_soff += a_step;
         b_soff += b_step;
     };
