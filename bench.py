@@ -33,8 +33,8 @@ MEASURED_TRAFFIC_BYTES = {
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", default="cfg2", help="cfg1..cfg5 (default cfg2, the QKV shard)")
     ap.add_argument("--all-configs", action="store_true", help="also time cfg2..cfg5 and report them under 'configs'")
     ap.add_argument("--no-cpu-baseline", action="store_true")

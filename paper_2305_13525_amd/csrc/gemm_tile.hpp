@@ -129,18 +129,6 @@ __device__ __forceinline__ void load_offsets(int tid, int64_t ld, uint32_t* off)
     }
 }
 
-// Copies one operand tile of one reduction step into LDS: round j of wave w lands at
-// lds_tile + (j * 512 + w * 64 + lane) * 16.  `soff` is the scalar byte offset of the step.
-template <int ROUNDS>
-__device__ __forceinline__ void issue_loads(__amdgpu_buffer_rsrc_t rsrc, const uint32_t* off, uint32_t soff,
-                                            char* lds_tile, int wave) {
-#pragma unroll
-    for (int j = 0; j < ROUNDS; ++j) {
-        char* dst = lds_tile + (j * TILE_THREADS + wave * 64) * 16;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)dst, 16, off[j], soff, 0, 0);
-    }
-}
-
 // LDS byte addresses from which this lane reads its MFMA fragments of one operand in one stage.
 // A 16x16x32 fragment is 8 consecutive reduction elements (lane/16 selects which 8 of the 32) of
 // row/column lane%16 of the tile.  KC: one address per 32-wide reduction sub-step (the tile
@@ -192,9 +180,14 @@ struct FragAddr {
     }
 };
 
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;  // a buffer resource descriptor in four SGPRs
+template <int V>
+using IC = std::integral_constant<int, V>;
+
 // Tells the scheduler to deal the memory instructions of a group out between its MFMAs: one MFMA
-// occupies the matrix pipe for 32 cycles, the wave can issue loads and LDS reads in that shadow,
-// and the other wave of the SIMD fills the pipe meanwhile.
+// occupies the matrix pipe for 16 cycles, the wave can issue LDS reads in that shadow, and the
+// other wave of the SIMD fills the pipe meanwhile.  (The direct-to-LDS loads are inline assembly
+// and stay where the source puts them: at the head of their group.)
 template <int N_MFMA, int N_VMEM, int N_DS, int I>
 struct Interleave {
     static __device__ __forceinline__ void run() {
@@ -225,8 +218,19 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     // global side: descriptor at the tile origin, per-lane offsets, scalar step
     const bf16_t* Ab = (LA == KC) ? g.A + (int64_t)i0 * g.lda : g.A + i0;
     const bf16_t* Bb = (LB == KC) ? g.B + (int64_t)j0 * g.ldb : g.B + j0;
-    const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Ab), 0, 0xFFFFFFFFu, 0x00020000);
-    const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Bb), 0, 0xFFFFFFFFu, 0x00020000);
+    // raw buffer descriptor: base, stride 0, no bound (the host checked the spans), dword format
+    auto make_rsrc = [](const bf16_t* p) __attribute__((always_inline)) {
+        const uint64_t v = reinterpret_cast<uint64_t>(p);
+        u32x4_t r;
+        r[0] = __builtin_amdgcn_readfirstlane((uint32_t)v);
+        r[1] = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32) & 0xFFFFu);
+        r[2] = 0xFFFFFFFFu;
+        r[3] = 0x00020000u;
+        return r;
+    };
+    const u32x4_t a_rsrc = make_rsrc(Ab);
+    const u32x4_t b_rsrc = make_rsrc(Bb);
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
     const uint32_t a_step = (uint32_t)((LA == KC) ? TILE_BK * 2 : (int64_t)TILE_BK * g.lda * 2);
     const uint32_t b_step = (uint32_t)((LB == KC) ? TILE_BK * 2 : (int64_t)TILE_BK * g.ldb * 2);
     uint32_t a_off[C::A_ROUNDS], b_off[C::B_ROUNDS];
@@ -271,29 +275,65 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     constexpr int RD_A = (LA == KC ? 1 : 2) * C::AH, RD_B = (LB == KC ? 1 : 2) * C::TN;
     uint32_t a_soff = 0, b_soff = 0;  // scalar byte offsets of the reduction step being loaded
     constexpr int NL = C::LOADS_PER_STAGE;
-    auto issue_stage = [&](int s) __attribute__((always_inline)) {
-        issue_loads<C::A_ROUNDS>(a_rsrc, a_off, a_soff, smem + s * C::A_BYTES, wave);
-        issue_loads<C::B_ROUNDS>(b_rsrc, b_off, b_soff, smem + 2 * C::A_BYTES + s * C::B_BYTES, wave);
+    // One direct-to-LDS load: 16 bytes per lane from descriptor base + off + soff to LDS address
+    // M0 + 16 * lane.  Issued through inline assembly on purpose: for a load the compiler knows
+    // to write LDS it puts a full vmcnt(0) wait in front of every later transposing LDS read,
+    // which stalls the wave for a whole memory latency in every step.  The kernel keeps the
+    // ordering itself: the vmcnt(0) wait and the barrier before the last MFMA group of each step.
+    auto load_lds = [](uint32_t lds_dst, uint32_t off, u32x4_t rsrc, uint32_t soff) __attribute__((always_inline)) {
+        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :
+                     : "s"(lds_dst), "v"(off), "s"(rsrc), "s"(soff)
+                     : "memory", "m0");
+    };
+    // Loads LO..HI-1 of the NL loads that fill stage s with the step at (a_soff, b_soff): the A
+    // rounds first, then the B rounds; round j of wave w lands at tile + (j * 512 + w * 64 + lane) * 16.
+    auto issue_range = [&](auto lo_tag, auto hi_tag, int s) __attribute__((always_inline)) {
+        constexpr int LO = decltype(lo_tag)::value, HI = decltype(hi_tag)::value;
+#pragma unroll
+        for (int j = LO; j < HI; ++j) {
+            if (j < C::A_ROUNDS) {
+                load_lds(smem_base + s * C::A_BYTES + (j * TILE_THREADS + wave * 64) * 16, a_off[j], a_rsrc, a_soff);
+            } else {
+                const int jb = j - C::A_ROUNDS;
+                load_lds(smem_base + 2 * C::A_BYTES + s * C::B_BYTES + (jb * TILE_THREADS + wave * 64) * 16,
+                         b_off[jb], b_rsrc, b_soff);
+            }
+        }
+    };
+    auto advance = [&]() __attribute__((always_inline)) {
         a_soff += a_step;
         b_soff += b_step;
     };
+    // A stage's loads are dealt out over three MFMA groups instead of one burst: half right after
+    // the barrier that frees the stage, a quarter in each of the first two groups of the next
+    // step.  The texture addresser takes one 1 KB wave-load per ~20 cycles, so eight waves that
+    // all issue their loads after the barrier block each other (and their MFMAs) for most of a
+    // group; the third group of the next step stays free of loads to cover their latency.
+    constexpr int E4 = (NL + 1) / 2, E1 = E4 + (NL - E4 + 1) / 2, E2 = NL;
 
     // One reduction step held in stage s (compile-time).  On entry the fragments of sub-step 0
     // are in register set 0.  The workgroup barrier sits before the last MFMA group: at that
     // point this wave has read all its fragments of stage s and has seen its own copies of stage
-    // s^1 land, so after the barrier stage s can be refilled (step j+2) and stage s^1 read; both
-    // are issued in the shadow of the last MFMA group.
+    // s^1 land, so after the barrier stage s can be refilled (step j+2) and stage s^1 read.
+    // `head`: the previous step began a refill of stage s^1 that this step has to finish;
+    // `load`: begin the refill of stage s; `next`: read the first fragments of the next step.
     // Wave priorities fall through the step and are highest right after the barrier: of the two
     // waves of a SIMD the one that lags is then preferred by the MFMA arbiter, which keeps them
     // from serialising (measured: without this one wave of each SIMD waits at the barrier for
     // about 40 % of the step while the other one is starved of MFMA issue slots).
-    auto step = [&](auto s_tag, const bool load, const bool next) __attribute__((always_inline)) {
+    auto step = [&](auto s_tag, const bool head, const bool load, const bool next) __attribute__((always_inline)) {
         constexpr int s = decltype(s_tag)::value;
         AXO_SETPRIO(2);
+        if (head) issue_range(IC<E4>{}, IC<E1>{}, s ^ 1);
         read_a(1, s, 0, 1);
         mfma_group(0, 0, 0);  // (kq 0, ah 0)
         Interleave<N_MFMA, 0, RD_A, 0>::run();
         AXO_SETPRIO(1);
+        if (head) {
+            issue_range(IC<E1>{}, IC<E2>{}, s ^ 1);
+            advance();
+        }
         read_a(0, s, 1, 0);
         read_b(1, s, 1);
         mfma_group(1, 0, 1);  // (kq 0, ah 1)
@@ -305,30 +345,31 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
         __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
         __syncthreads();
         AXO_SETPRIO(3);
-        if (load) issue_stage(s);
+        if (load) issue_range(IC<0>{}, IC<E4>{}, s);
         if (next) {
             read_a(0, s ^ 1, 0, 0);
             read_b(0, s ^ 1, 0);
         }
         mfma_group(1, 1, 1);  // (kq 1, ah 1)
-        Interleave<N_MFMA, NL, RD_A + RD_B, 0>::run();
+        Interleave<N_MFMA, 0, RD_A + RD_B, 0>::run();
     };
     using T0 = std::integral_constant<int, 0>;
     using T1 = std::integral_constant<int, 1>;
 
     // KT is even and at least 2 (the host only sends reductions that are multiples of 128 here)
-    issue_stage(0);
-    issue_stage(1);
-    AXO_WAIT_VMCNT(C::LOADS_PER_STAGE);  // step 0 has landed, step 1 may be in flight
+    issue_range(IC<0>{}, IC<NL>{}, 0);
+    advance();
+    issue_range(IC<0>{}, IC<E4>{}, 1);  // step 0 issues the rest of stage 1
+    AXO_WAIT_VMCNT(E4);                 // stage 0 has landed
     __syncthreads();
     read_a(0, 0, 0, 0);
     read_b(0, 0, 0);
     for (int j = 0; j + 2 < KT; j += 2) {  // steady state, branch free: steps j, j+1; refills j+2, j+3
-        step(T0{}, true, true);
-        step(T1{}, true, true);
+        step(T0{}, true, true, true);
+        step(T1{}, true, true, true);
     }
-    step(T0{}, false, true);  // the last two steps: nothing left to load
-    step(T1{}, false, false);
+    step(T0{}, true, false, true);  // the last two steps: nothing left to load
+    step(T1{}, false, false, false);
     AXO_SETPRIO(0);
 
     // ---- epilogue: acc[a][b][e] is C[i0 + wm*WTM + a*16 + lane%16][j0 + wn*WTN + b*16 + 4*(lane/16) + e]
