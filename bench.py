@@ -24,9 +24,9 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
 # WRITE_SIZE runs of this script, scaled by the same counters' readings for a plain 1 GiB copy
 # (2.000 KiB per FETCH_SIZE count, 1.000 KiB per WRITE_SIZE count).  Keyed by (workload, product).
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg2", "fwd"): int((83053.48 * 2.0 + 49152.0) * 1024),
-    ("cfg2", "dgrad"): int((98652.57 * 2.0 + 16384.0) * 1024),
-    ("cfg2", "wgrad"): int((82589.72 * 2.0 + 24576.0) * 1024),
+    ("cfg2", "fwd"): int((82587.28 * 2.0 + 49152.0) * 1024),
+    ("cfg2", "dgrad"): int((98375.23 * 2.0 + 16384.0) * 1024),
+    ("cfg2", "wgrad"): int((82019.37 * 2.0 + 24576.0) * 1024),
 }
 
 
