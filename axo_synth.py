@@ -163,7 +163,8 @@ def global_inputs(layer: Layer) -> Dict[str, np.ndarray]:
     return layer_inputs(one)
 
 
-# The five benchmark configurations.  Each is a list of layers (a chain for cfg5).
+# The five benchmark configurations and the paper's running example.  Each is a list of layers
+# (a chain for cfg5 and gpt20b).
 def configs() -> Dict[str, List[Layer]]:
     return {
         "cfg1": [Layer("fc", (1, 1, 1), 512, 1024, 1024)],
@@ -176,6 +177,14 @@ def configs() -> Dict[str, List[Layer]]:
             Layer("attn_out", (8, 8, 4), 16384, 12288, 12288, EPI_NONE, 0, 1),
             Layer("mlp_up", (8, 8, 4), 16384, 12288, 49152, EPI_BIAS_GELU_TANH, 0, 2),
             Layer("mlp_down", (8, 8, 4), 16384, 49152, 12288, EPI_NONE, 0, 3),
+        ],
+        # The running example of Section 4: a 20B-parameter GPT (Table 1: hidden size 7168), a
+        # batch of 32k tokens, Gx = Gy = 2, Gz = 4 on 16 GPUs; the four FC layers of one block.
+        "gpt20b": [
+            Layer("qkv", (2, 2, 4), 32768, 7168, 21504, EPI_NONE, 0, 0),
+            Layer("attn_out", (2, 2, 4), 32768, 7168, 7168, EPI_NONE, 0, 1),
+            Layer("mlp_up", (2, 2, 4), 32768, 7168, 28672, EPI_BIAS_GELU_TANH, 0, 2),
+            Layer("mlp_down", (2, 2, 4), 32768, 28672, 7168, EPI_NONE, 0, 3),
         ],
     }
 

@@ -2,11 +2,12 @@
 """Benchmark of the shard-GEMM hot path on one MI355X.
 
 A step is one pass of the hot path over one workload: the forward, dgrad and wgrad local
-products of a 3D-tensor-parallel FC layer shard (for the chain workload: axo_layer_step over all
-layers).  Inputs are seeded synthetic bf16 shards, resident in HBM before the timed region.
-Prints one JSON line: TFLOP/s of the step (2*M*Kl*Nl flop per product), a roofline object for the
-slowest product's kernel (HIP-event timed on the launch stream) and the CPU oracle timed on a
-bounded sample of the same workload.
+products of a 3D-tensor-parallel FC layer shard (for the chain workloads: of every layer), through
+axo_layer_step_grouped (default: one launch over the tiles of all products) or axo_layer_step
+(--step sequential: one launch per product).  Inputs are seeded synthetic bf16 shards, resident
+in HBM before the timed region.  Prints one JSON line: TFLOP/s of the step (2*M*Kl*Nl flop per
+product), a roofline object for the dominant kernel (HIP-event timed on the launch stream) and the
+CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -22,11 +23,13 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
 
 # HBM-side bytes per launch (fetched + written) of the tuned kernel, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script, scaled by the same counters' readings for a plain 1 GiB copy
-# (2.000 KiB per FETCH_SIZE count, 1.000 KiB per WRITE_SIZE count).  Keyed by (workload, product).
+# (2.000 KiB per FETCH_SIZE count, 1.000 KiB per WRITE_SIZE count).  Keyed by (workload, product);
+# "group" is the single launch of the grouped step.
 MEASURED_TRAFFIC_BYTES = {
     ("cfg2", "fwd"): int((82587.28 * 2.0 + 49152.0) * 1024),
     ("cfg2", "dgrad"): int((98375.23 * 2.0 + 16384.0) * 1024),
     ("cfg2", "wgrad"): int((82019.37 * 2.0 + 24576.0) * 1024),
+    ("cfg2", "group"): int((309812.07 * 2.0 + 90112.0) * 1024),
 }
 
 
@@ -36,7 +39,11 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", default="cfg2", help="cfg1..cfg5 (default cfg2, the QKV shard)")
-    ap.add_argument("--all-configs", action="store_true", help="also time cfg2..cfg5 and report them under 'configs'")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time cfg2..cfg5 and gpt20b and report them under 'configs'")
+    ap.add_argument("--step", choices=("sequential", "grouped"), default="grouped",
+                    help="entry point of the timed step: axo_layer_step_grouped (one launch over the tiles of all "
+                         "products; the default) or axo_layer_step (one launch per product, in order)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE readings)")
@@ -80,15 +87,17 @@ def main() -> int:
         keep.append(ws)
         return layers, objs, keep, flop, ws.data_ptr(), nws
 
+    step_fn = axo.axo_layer_step if args.step == "sequential" else axo.axo_layer_step_grouped
+
     def time_step(objs, wsp, nws, steps, warmup):
         for _ in range(warmup):
-            axo.axo_layer_step(objs, wsp, nws, st)
+            step_fn(objs, wsp, nws, st)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
         e0.record()
         for _ in range(steps):
-            axo.axo_layer_step(objs, wsp, nws, st)
+            step_fn(objs, wsp, nws, st)
         e1.record()
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3
@@ -129,33 +138,46 @@ def main() -> int:
     ms, wall_ms = time_step(objs, wsp, nws, args.steps, args.warmup)
     tflops = flop / (ms * 1e-3) / 1e12
 
-    # dominant kernel: the slowest of the products of the first (for cfg5: the largest) layer
+    # per-product launches of the largest layer, each timed in a loop of its own
     li = max(range(len(layers)), key=lambda i: layers[i].flop_per_gemm)
     ops = per_op(layers[li], objs[li], wsp, nws, args.steps, args.warmup)
-    dom = max(ops, key=ops.get)
     gflop = layers[li].flop_per_gemm
-    ach = gflop / (ops[dom] * 1e-3) / 1e12
-    M, Kl, Nl = layers[li].shard
-    roofline = {"bound": "mfma", "kernel": f"{layers[li].name}.{dom}", "achieved": round(ach, 2),
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, dom)), "flop_per_launch": gflop, "avg_launch_ms": round(ops[dom], 5),
-                "algorithmic_bytes_per_launch": 2 * (M * Kl + Kl * Nl + M * Nl),
-                "per_op_ms": {k: round(v, 5) for k, v in ops.items()},
-                "per_op_tflops": {k: round(gflop / (v * 1e-3) / 1e12, 2) for k, v in ops.items()}}
+    per_op_info = {"layer": layers[li].name,
+                   "per_op_ms": {k: round(v, 5) for k, v in ops.items()},
+                   "per_op_tflops": {k: round(gflop / (v * 1e-3) / 1e12, 2) for k, v in ops.items()}}
+    alg_bytes = sum(2 * (L.shard[0] * L.shard[1] + L.shard[1] * L.shard[2] + L.shard[0] * L.shard[2]) for L in layers)
+    if args.step == "grouped" and len(layers) <= 4:
+        # the whole step is ONE launch of gemm_group_kernel: its duration is the step's
+        roofline = {"bound": "mfma", "kernel": "gemm_group_kernel (all products of the step)",
+                    "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tflops / PEAK_BF16_TFLOPS, 4),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, "group")), "flop_per_launch": flop,
+                    "avg_launch_ms": round(ms, 5), "algorithmic_bytes_per_launch": 3 * alg_bytes}
+    else:
+        # one launch per product: the dominant kernel is the slowest product of the largest layer
+        dom = max(ops, key=ops.get)
+        ach = gflop / (ops[dom] * 1e-3) / 1e12
+        M, Kl, Nl = layers[li].shard
+        roofline = {"bound": "mfma", "kernel": f"gemm_mixed_kernel ({layers[li].name}.{dom})", "achieved": round(ach, 2),
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, dom)), "flop_per_launch": gflop,
+                    "avg_launch_ms": round(ops[dom], 5),
+                    "algorithmic_bytes_per_launch": 2 * (M * Kl + Kl * Nl + M * Nl)}
+    roofline["separate_launches"] = per_op_info
 
     out = {"metric": "TFLOP/s for fwd+dgrad+wgrad shard GEMMs, 1 MI355X", "value": round(tflops, 2),
            "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms, 5), "wall_ms_per_step": round(wall_ms, 5), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
-           "config": {"workload": args.config, "layers": [
+           "config": {"workload": args.config, "step": args.step, "layers": [
                {"name": L.name, "grid": list(L.grid), "shard_MKN": list(L.shard), "epilogue": L.epilogue}
                for L in layers], "flop_per_step": flop},
            "roofline": roofline}
 
     if args.all_configs:
         extra = {}
-        for name in ("cfg2", "cfg3", "cfg4", "cfg5"):
+        for name in ("cfg2", "cfg3", "cfg4", "cfg5", "gpt20b"):
             if name == args.config:
                 extra[name] = {"tflops": round(tflops, 2), "ms_per_step": round(ms, 5)}
                 continue

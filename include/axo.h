@@ -158,6 +158,18 @@ size_t axo_layer_step_workspace_bytes(const axo_layer_t *layers, int n_layers);
 int axo_layer_step(const axo_layer_t *layers, int n_layers, void *ws, size_t ws_bytes,
                    void *hip_stream);
 
+/* The same products with the same results, bit for bit, as axo_layer_step, for chains whose
+ * products are independent of each other: NO output buffer of the call (any layer's Y, dX, dW)
+ * may overlap an input buffer of the call (any layer's X, W, bias, dY).  Under that condition the
+ * 3 * n_layers local products of Algorithm 1 can run in any order, and the library enqueues them
+ * as grouped launches: the output tiles of up to 12 products share one grid, most expensive tiles
+ * first, so that products too small to fill the GPU on their own (a 1536 x 1536 shard is 36 tiles
+ * for 256 compute units) run side by side and the chain pays one ramp-up and one tail instead of
+ * one per product.  Products whose shapes the tiled kernel does not take are launched on their
+ * own.  Validation, workspace, stream and error behaviour are those of axo_layer_step. */
+int axo_layer_step_grouped(const axo_layer_t *layers, int n_layers, void *ws, size_t ws_bytes,
+                           void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -86,6 +86,8 @@ def library() -> ctypes.CDLL:
     L.axo_layer_step_workspace_bytes.restype = sz
     L.axo_layer_step.argtypes = [ctypes.POINTER(Layer), i32, vp, sz, vp]
     L.axo_layer_step.restype = i32
+    L.axo_layer_step_grouped.argtypes = [ctypes.POINTER(Layer), i32, vp, sz, vp]
+    L.axo_layer_step_grouped.restype = i32
     _lib = L
     return L
 
@@ -153,3 +155,9 @@ def axo_layer_step(layers: Sequence[Layer], ws: Optional[int] = None, ws_bytes: 
                    stream: Optional[int] = None, check: bool = True) -> int:
     rc = library().axo_layer_step(_layer_array(layers), len(layers), ws, ws_bytes, stream)
     return _check(rc, "axo_layer_step", check)
+
+
+def axo_layer_step_grouped(layers: Sequence[Layer], ws: Optional[int] = None, ws_bytes: int = 0,
+                           stream: Optional[int] = None, check: bool = True) -> int:
+    rc = library().axo_layer_step_grouped(_layer_array(layers), len(layers), ws, ws_bytes, stream)
+    return _check(rc, "axo_layer_step_grouped", check)

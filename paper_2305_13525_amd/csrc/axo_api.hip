@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cstdlib>
 #include <functional>
@@ -169,6 +170,90 @@ int launch_tile_layout(const GemmArgs& g, int la, int lb, hipStream_t st) {
     return launch_tile<axo::MC, axo::MC>(g, st);
 }
 
+// ---- grouped launch ------------------------------------------------------------------------
+// Cost of one tile in reduction steps of a big tile: the steps themselves plus a fixed share for
+// the tile's first loads and its epilogue (measured: a two-step tile takes about as long as six
+// steps of a long one).
+constexpr double TILE_OVERHEAD_STEPS = 4.0;
+double tile_cost(int R, bool small) {
+    return (R / (double)axo::TILE_BK + TILE_OVERHEAD_STEPS) * (small ? SMALL_TILE_COST : 1.0);
+}
+
+int layout_pair(int la, int lb) { return (la == axo::KC && lb == axo::MC) ? 0 : (la == axo::KC ? 1 : 2); }
+
+struct GroupItem {
+    int Mo, No, R, pair;
+    bool operator<(const GroupItem& o) const {
+        if (Mo != o.Mo) return Mo < o.Mo;
+        if (No != o.No) return No < o.No;
+        if (R != o.R) return R < o.R;
+        return pair < o.pair;
+    }
+};
+
+struct SegCost {
+    double cost;
+    int count, item, small;
+};
+
+// segments of a group for a choice of big_cols per item, most expensive tiles first
+std::vector<SegCost> group_segments(const std::vector<GroupItem>& items, const std::vector<int>& big_cols) {
+    std::vector<SegCost> segs;
+    for (size_t i = 0; i < items.size(); ++i) {
+        const int tiles_m = items[i].Mo / 256, cb = big_cols[i], cs = (items[i].No - cb * 256) / 128;
+        if (cb > 0) segs.push_back({tile_cost(items[i].R, false), tiles_m * cb, (int)i, 0});
+        if (cs > 0) segs.push_back({tile_cost(items[i].R, true), tiles_m * cs, (int)i, 1});
+    }
+    std::stable_sort(segs.begin(), segs.end(), [](const SegCost& a, const SegCost& b) { return a.cost > b.cost; });
+    return segs;
+}
+
+double group_makespan(const std::vector<SegCost>& segs) {
+    std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
+    for (int i = 0; i < NUM_CU; ++i) free_at.push(0.0);
+    double end = 0.0;
+    for (const SegCost& sg : segs)
+        for (int i = 0; i < sg.count; ++i) {
+            const double t = free_at.top() + sg.cost;
+            free_at.pop();
+            free_at.push(t);
+            if (t > end) end = t;
+        }
+    return end;
+}
+
+// big_cols per item that minimise the simulated makespan of the whole group: coordinate descent
+// from "all big tiles", two sweeps.  Cached per list of shapes.
+std::vector<int> plan_group(const std::vector<GroupItem>& items) {
+    static std::mutex mu;
+    static std::map<std::vector<GroupItem>, std::vector<int>> cache;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = cache.find(items);
+    if (it != cache.end()) return it->second;
+    std::vector<int> cols(items.size());
+    for (size_t i = 0; i < items.size(); ++i) cols[i] = items[i].No / 256;
+    double best = group_makespan(group_segments(items, cols));
+    for (int sweep = 0; sweep < 2; ++sweep)
+        for (size_t i = 0; i < items.size(); ++i) {
+            const int max_cols = items[i].No / 256;
+            const int stride = max_cols > 16 ? (max_cols + 15) / 16 : 1;
+            int best_c = cols[i];
+            for (int c = max_cols; c >= 0; c -= stride) {
+                cols[i] = c;
+                const double t = group_makespan(group_segments(items, cols));
+                if (t < best - 1e-9) {
+                    best = t;
+                    best_c = c;
+                }
+            }
+            cols[i] = best_c;
+        }
+    if (cache.size() < 1024) cache[items] = cols;
+    return cols;
+}
+
+// One launch over the tiles of all given products (each tileable and non-empty, at most
+// GROUP_MAX_PRODUCTS of them).
 bool force_generic() {
     static const bool v = [] { const char* e = getenv("AXO_FORCE_GENERIC"); return e && e[0] == '1'; }();
     return v;
@@ -194,6 +279,40 @@ struct Plan {
     int la, lb;
 };
 
+int launch_group(const Plan* const* plans, int n, hipStream_t st) {
+    static std::atomic<int> ready{0};
+    if (!ready.load(std::memory_order_acquire)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(axo::gemm_group_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, axo::MIX_LDS_BYTES) != hipSuccess)
+            return AXO_ERR_HIP;
+        ready.store(1, std::memory_order_release);
+    }
+    std::vector<GroupItem> items(n);
+    for (int i = 0; i < n; ++i)
+        items[i] = {plans[i]->g.Mo, plans[i]->g.No, plans[i]->g.R, layout_pair(plans[i]->la, plans[i]->lb)};
+    const std::vector<int> cols = plan_group(items);
+    const std::vector<SegCost> segs = group_segments(items, cols);
+    axo::GroupArgs ga{};
+    ga.n_seg = (int)segs.size();
+    int blocks = 0;
+    for (int k = 0; k < ga.n_seg; ++k) {
+        const SegCost& sc = segs[k];
+        axo::GroupSeg& sg = ga.seg[k];
+        sg.first_block = blocks;
+        sg.n_blocks = sc.count;
+        sg.product = sc.item;
+        sg.kind = 2 * items[sc.item].pair + sc.small;
+        sg.tiles_m = items[sc.item].Mo / 256;
+        sg.cols = sc.count / sg.tiles_m;
+        sg.col0 = sc.small ? cols[sc.item] * 256 : 0;
+        sg.group_m = sg.tiles_m < 4 ? sg.tiles_m : 4;
+        blocks += sc.count;
+    }
+    for (int i = 0; i < n; ++i) ga.g[i] = plans[i]->g;
+    hipLaunchKernelGGL(axo::gemm_group_kernel, dim3(blocks), dim3(axo::TILE_THREADS), axo::MIX_LDS_BYTES, st, ga);
+    return hipGetLastError() == hipSuccess ? AXO_OK : AXO_ERR_HIP;
+}
+
 int plan_fwd(const axo_problem_t* p, const void* X, int64_t ldx, const void* W, int64_t ldw, const void* bias,
              int epilogue, void* Y, int64_t ldy, void* ws, size_t ws_bytes, Plan* out) {
     Shard s;
@@ -214,7 +333,6 @@ int plan_fwd(const axo_problem_t* p, const void* X, int64_t ldx, const void* W, 
     g.Mo = (int)s.M; g.No = (int)s.Nl; g.R = (int)s.Kl;
     g.epilogue = epilogue;
     g.add_bias = (epilogue != AXO_EPI_NONE && s.k_coord == 0) ? 1 : 0;
-    g.ws = static_cast<float*>(ws); g.splits = 1;
     out->la = axo::KC; out->lb = axo::MC;
     return AXO_OK;
 }
@@ -235,7 +353,6 @@ int plan_dgrad(const axo_problem_t* p, const void* dY, int64_t lddy, const void*
     g.bias = nullptr;
     g.Mo = (int)s.M; g.No = (int)s.Kl; g.R = (int)s.Nl;
     g.epilogue = AXO_EPI_NONE; g.add_bias = 0;
-    g.ws = static_cast<float*>(ws); g.splits = 1;
     out->la = axo::KC; out->lb = axo::KC;
     return AXO_OK;
 }
@@ -256,8 +373,30 @@ int plan_wgrad(const axo_problem_t* p, const void* X, int64_t ldx, const void* d
     g.bias = nullptr;
     g.Mo = (int)s.Kl; g.No = (int)s.Nl; g.R = (int)s.M;
     g.epilogue = AXO_EPI_NONE; g.add_bias = 0;
-    g.ws = static_cast<float*>(ws); g.splits = 1;
     out->la = axo::MC; out->lb = axo::MC;
+    return AXO_OK;
+}
+
+// Validates a chain and lists its products in the order of Section 4.1: forwards of layers
+// 0..n-1, then for layers n-1..0 dgrad followed by wgrad.  Nothing is launched here, so a chain
+// with a malformed product enqueues nothing.
+int plan_chain(const axo_layer_t* layers, int n_layers, void* ws, size_t ws_bytes, std::vector<Plan>* out) {
+    if (n_layers < 0) return AXO_ERR_BAD_ARG;
+    if (n_layers == 0) return AXO_OK;
+    if (!layers) return AXO_ERR_NULL_PTR;
+    if (n_layers > 4096) return AXO_ERR_BAD_ARG;
+    out->resize(3 * (size_t)n_layers);
+    for (int i = 0; i < n_layers; ++i) {
+        const axo_layer_t& L = layers[i];
+        if (L.reserved != 0) return AXO_ERR_BAD_ARG;
+        int rc = plan_fwd(&L.p, L.X, L.ldx, L.W, L.ldw, L.bias, L.epilogue, L.Y, L.ldy, ws, ws_bytes, &(*out)[i]);
+        if (rc) return rc;
+        const size_t b = (size_t)n_layers + 2 * (size_t)(n_layers - 1 - i);
+        rc = plan_dgrad(&L.p, L.dY, L.lddy, L.W, L.ldw, L.dX, L.lddx, ws, ws_bytes, &(*out)[b]);
+        if (rc) return rc;
+        rc = plan_wgrad(&L.p, L.X, L.ldx, L.dY, L.lddy, L.dW, L.lddw, ws, ws_bytes, &(*out)[b + 1]);
+        if (rc) return rc;
+    }
     return AXO_OK;
 }
 
@@ -342,30 +481,35 @@ size_t axo_layer_step_workspace_bytes(const axo_layer_t* layers, int n_layers) {
 }
 
 int axo_layer_step(const axo_layer_t* layers, int n_layers, void* ws, size_t ws_bytes, void* hip_stream) {
-    if (n_layers < 0) return AXO_ERR_BAD_ARG;
-    if (n_layers == 0) return AXO_OK;
-    if (!layers) return AXO_ERR_NULL_PTR;
-    if (n_layers > 4096) return AXO_ERR_BAD_ARG;
-    // validate the whole chain first: nothing is enqueued unless every product is well formed
-    Plan* plans = new (std::nothrow) Plan[3 * (size_t)n_layers];
-    if (!plans) return AXO_ERR_BAD_ARG;
-    int rc = AXO_OK;
-    for (int i = 0; i < n_layers && rc == AXO_OK; ++i) {
-        const axo_layer_t& L = layers[i];
-        if (L.reserved != 0) { rc = AXO_ERR_BAD_ARG; break; }
-        rc = plan_fwd(&L.p, L.X, L.ldx, L.W, L.ldw, L.bias, L.epilogue, L.Y, L.ldy, ws, ws_bytes, &plans[3 * i]);
-        if (rc) break;
-        rc = plan_dgrad(&L.p, L.dY, L.lddy, L.W, L.ldw, L.dX, L.lddx, ws, ws_bytes, &plans[3 * i + 1]);
-        if (rc) break;
-        rc = plan_wgrad(&L.p, L.X, L.ldx, L.dY, L.lddy, L.dW, L.lddw, ws, ws_bytes, &plans[3 * i + 2]);
-    }
+    std::vector<Plan> plans;
+    int rc = plan_chain(layers, n_layers, ws, ws_bytes, &plans);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    for (int i = 0; i < n_layers && rc == AXO_OK; ++i) rc = launch(plans[3 * i].g, plans[3 * i].la, plans[3 * i].lb, st);
-    for (int i = n_layers - 1; i >= 0 && rc == AXO_OK; --i) {
-        rc = launch(plans[3 * i + 1].g, plans[3 * i + 1].la, plans[3 * i + 1].lb, st);
-        if (rc == AXO_OK) rc = launch(plans[3 * i + 2].g, plans[3 * i + 2].la, plans[3 * i + 2].lb, st);
+    for (size_t i = 0; i < plans.size() && rc == AXO_OK; ++i) rc = launch(plans[i].g, plans[i].la, plans[i].lb, st);
+    return rc;
+}
+
+int axo_layer_step_grouped(const axo_layer_t* layers, int n_layers, void* ws, size_t ws_bytes, void* hip_stream) {
+    std::vector<Plan> plans;
+    int rc = plan_chain(layers, n_layers, ws, ws_bytes, &plans);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    std::vector<const Plan*> group;
+    auto flush = [&]() {
+        if (group.empty() || rc != AXO_OK) return;
+        rc = group.size() == 1 ? launch_tile_layout(group[0]->g, group[0]->la, group[0]->lb, st)
+                               : launch_group(group.data(), (int)group.size(), st);
+        group.clear();
+    };
+    for (size_t i = 0; i < plans.size() && rc == AXO_OK; ++i) {
+        const Plan& pl = plans[i];
+        if (pl.g.Mo == 0 || pl.g.No == 0) continue;
+        if (!tileable(pl.g, pl.la, pl.lb) || force_generic()) {
+            rc = launch_generic(pl.g, pl.la, pl.lb, st);
+            continue;
+        }
+        group.push_back(&pl);
+        if ((int)group.size() == axo::GROUP_MAX_PRODUCTS) flush();
     }
-    delete[] plans;
+    flush();
     return rc;
 }
 

@@ -32,8 +32,6 @@ struct GemmArgs {
     int Mo, No, R;       // output rows, output cols, reduction length
     int epilogue;        // Epilogue
     int add_bias;        // 0: bias pointer ignored (shard is not at K-coordinate 0)
-    float* ws;           // fp32 partial sums for split reductions (or nullptr)
-    int splits;          // number of reduction splits (1 = none)
 };
 
 __device__ __forceinline__ float bf16_bits_to_f32(bf16_t b) {

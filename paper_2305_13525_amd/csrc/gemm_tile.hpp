@@ -448,4 +448,51 @@ __global__ void __launch_bounds__(TILE_THREADS, 1) gemm_mixed_kernel(GemmArgs g,
     }
 }
 
+// ---- grouped launch: the tiles of several independent products in one grid ----------------
+// A product on its own often cannot fill the 256 CUs (a 1536x1536 output is 36 big tiles), and a
+// chain of such launches pays a ramp-up and a tail each.  A group launch strings the tile lists of
+// up to GROUP_MAX_PRODUCTS products together: the grid is cut into segments, a segment is all the
+// tiles of one size of one product, and segments are ordered by decreasing tile cost so that the
+// in-order workgroup dispatch approximates longest-processing-time-first scheduling.
+constexpr int GROUP_MAX_PRODUCTS = 12;
+constexpr int GROUP_MAX_SEGMENTS = 2 * GROUP_MAX_PRODUCTS;
+
+struct GroupSeg {
+    int first_block;  // first workgroup id of the segment
+    int n_blocks;
+    int product;      // index into GroupArgs::g
+    int kind;         // 2 * layout pair (0: KC/MC, 1: KC/KC, 2: MC/MC) + (1 if 256x128 tiles)
+    int tiles_m;      // tile rows
+    int cols;         // tile columns of this segment
+    int col0;         // first output column of this segment
+    int group_m;      // band height of the tile order
+};
+
+struct GroupArgs {
+    int n_seg;
+    GroupSeg seg[GROUP_MAX_SEGMENTS];
+    GemmArgs g[GROUP_MAX_PRODUCTS];
+};
+
+__global__ void __launch_bounds__(TILE_THREADS, 1) gemm_group_kernel(GroupArgs ga) {
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int bid = blockIdx.x;
+    int si = 0;
+    for (int i = 1; i < ga.n_seg; ++i)
+        if (bid >= ga.seg[i].first_block) si = i;
+    const GroupSeg sg = ga.seg[si];
+    const GemmArgs g = ga.g[sg.product];
+    int tm, tn;
+    // workgroup ids with equal id % 8 share an XCD whatever the segment's first id is
+    tile_of_index(xcd_contiguous(bid - sg.first_block, sg.n_blocks), sg.tiles_m, sg.cols, sg.group_m, tm, tn);
+    switch (sg.kind) {
+        case 0: gemm_tile_body<256, 256, 2, 4, KC, MC>(g, tm * 256, sg.col0 + tn * 256, smem); break;
+        case 1: gemm_tile_body<256, 128, 4, 2, KC, MC>(g, tm * 256, sg.col0 + tn * 128, smem); break;
+        case 2: gemm_tile_body<256, 256, 2, 4, KC, KC>(g, tm * 256, sg.col0 + tn * 256, smem); break;
+        case 3: gemm_tile_body<256, 128, 4, 2, KC, KC>(g, tm * 256, sg.col0 + tn * 128, smem); break;
+        case 4: gemm_tile_body<256, 256, 2, 4, MC, MC>(g, tm * 256, sg.col0 + tn * 256, smem); break;
+        default: gemm_tile_body<256, 128, 4, 2, MC, MC>(g, tm * 256, sg.col0 + tn * 128, smem); break;
+    }
+}
+
 }  // namespace axo

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"axo_fc_fwd", "axo_fc_dgrad", "axo_fc_wgrad", "axo_layer_step", "axo_shard_dims",
             "axo_workspace_bytes", "axo_status_string", "axo_version",
-            "axo_layer_step_workspace_bytes"} <= set(names)
+            "axo_layer_step_workspace_bytes", "axo_layer_step_grouped"} <= set(names)
     lib = ctypes.CDLL(axo.library_path())
     for n in names:
         assert hasattr(lib, n), n
@@ -148,20 +148,22 @@ def test_empty_shards_need_no_device():
     assert axo.axo_fc_wgrad(pn, A, 32, A, 8, A, 8, check=False) == OK
 
 
-def test_layer_step_validates_whole_chain_first():
+@pytest.mark.parametrize("entry", ["axo_layer_step", "axo_layer_step_grouped"])
+def test_layer_step_validates_whole_chain_first(entry):
+    step = getattr(axo, entry)
     # T == 0 and N == 0: none of the three products has an output element, so nothing launches
     good = axo.Layer(axo.Problem.make((1, 1, 1), (0, 0, 0), 0, 32, 0), 0, 0, A, 32, A, 8, None, A, 8, A, 8,
                      A, 32, A, 8)
     bad = axo.Layer(axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 48), 0, 0, A, 32, A, 48, None, A, 48, A, 48,
                     None, 32, A, 48)  # dX missing
-    assert axo.axo_layer_step([], check=False) == OK
-    assert axo.axo_layer_step([good], check=False) == OK  # empty shard: no launch
-    assert axo.axo_layer_step([good, bad], check=False) == NULL_PTR
+    assert step([], check=False) == OK
+    assert step([good], check=False) == OK  # empty shard: no launch
+    assert step([good, bad], check=False) == NULL_PTR
     worse = axo.Layer(axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 48), 9, 0, A, 32, A, 48, None, A, 48, A, 48,
                       A, 32, A, 48)
-    assert axo.axo_layer_step([worse], check=False) == BAD_EPI
-    assert axo.library().axo_layer_step(None, 2, None, 0, None) == NULL_PTR
-    assert axo.library().axo_layer_step(None, -1, None, 0, None) == BAD_ARG
+    assert step([worse], check=False) == BAD_EPI
+    assert getattr(axo.library(), entry)(None, 2, None, 0, None) == NULL_PTR
+    assert getattr(axo.library(), entry)(None, -1, None, 0, None) == BAD_ARG
     assert axo.axo_layer_step_workspace_bytes([good, bad]) >= 0
 
 

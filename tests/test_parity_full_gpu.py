@@ -15,7 +15,8 @@ torch = pytest.importorskip("torch")
 import gpu_util as gu  # noqa: E402
 
 
-def run_chain(layers):
+def run_chain(layers, step=None):
+    step = step or axo.axo_layer_step
     objs, keep = [], []
     for L in layers:
         d = syn.layer_inputs(L)
@@ -29,7 +30,7 @@ def run_chain(layers):
                               t["dY"].data_ptr(), Nl, t["dX"].data_ptr(), Kl, t["dW"].data_ptr(), Nl))
     nws = axo.axo_layer_step_workspace_bytes(objs)
     ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda:0")
-    axo.axo_layer_step(objs, ws.data_ptr(), nws, gu.stream())
+    step(objs, ws.data_ptr(), nws, gu.stream())
     torch.cuda.synchronize()
     return keep
 
@@ -74,3 +75,31 @@ def test_chain_equals_single_calls():
              gu.run_dgrad(p, t["dY"], t["W"], dX), gu.run_wgrad(p, t["X"], t["dY"], dW)]
         torch.cuda.synchronize()
         assert torch.equal(Y, t["Y"]) and torch.equal(dX, t["dX"]) and torch.equal(dW, t["dW"])
+
+
+def test_grouped_chain_cfg5_against_oracle():
+    """All 12 products of the chain in one grouped launch, sampled rows against the oracle."""
+    layers = syn.configs()["cfg5"]
+    keep = run_chain(layers, axo.axo_layer_step_grouped)
+    for L, (d, t) in zip(layers, keep):
+        check_sampled(L, d, t, 31 + L.layer_index)
+
+
+@pytest.mark.parametrize("cfg", ["cfg2", "cfg5", "gpt20b"])
+def test_grouped_equals_sequential(cfg):
+    """The grouped launch cuts the outputs into other tiles but every element is still reduced in
+    the same order by the same instructions: bit-identical to the sequential chain."""
+    layers = syn.configs()[cfg]
+    a = run_chain(layers)
+    b = run_chain(layers, axo.axo_layer_step_grouped)
+    for (_, ta), (_, tb) in zip(a, b):
+        for k in ("Y", "dX", "dW"):
+            assert torch.equal(ta[k], tb[k]), k
+
+
+def test_running_example_gpt20b():
+    """The (2,2,4) shards of the paper's GPT-20B running example (Section 4), sequential chain."""
+    layers = syn.configs()["gpt20b"]
+    keep = run_chain(layers)
+    for L, (d, t) in zip(layers, keep):
+        check_sampled(L, d, t, 41 + L.layer_index)

@@ -280,3 +280,30 @@ def test_rounding_is_nearest_even():
     want = syn.f32_to_bf16_bits(ref.astype(np.float32))  # every sum here is exact in fp32
     assert np.array_equal(Y, want)
     assert Y[0, 0] == 0x3F80 and Y[0, 3] == 0x3F80
+
+
+def test_grouped_step_mixed_shapes_against_oracle():
+    """axo_layer_step_grouped on a chain that mixes shapes the tiled kernel takes, shapes it does not
+    (ragged; a product with a 128-row output) and an empty layer: every element against the oracle."""
+    shapes = [(256, 256, 256), (300, 72, 136), (256, 128, 384), (512, 384, 640), (0, 64, 64), (768, 256, 1152)]
+    layers, keep = [], []
+    for i, (M, Kl, Nl) in enumerate(shapes):
+        Xb, Wb, dYb = rand_trio(M, Kl, Nl, 900 + i)
+        bias_b = syn.normal_bf16(900 + i, 3, (1, Nl), 0.5)[0]
+        epi = axo.AXO_EPI_BIAS_GELU_TANH if i % 2 else axo.AXO_EPI_NONE
+        t = dict(X=gu.to_dev(Xb), W=gu.to_dev(Wb), dY=gu.to_dev(dYb), bias=gu.to_dev(bias_b),
+                 Y=gu.empty_dev(M, Nl), dX=gu.empty_dev(M, Kl), dW=gu.empty_dev(Kl, Nl))
+        keep.append((Xb, Wb, dYb, bias_b, epi, t))
+        layers.append(axo.Layer(P(M, Kl, Nl), epi, 0, t["X"].data_ptr(), Kl, t["W"].data_ptr(), Nl,
+                                t["bias"].data_ptr() if epi else None, t["Y"].data_ptr(), Nl,
+                                t["dY"].data_ptr(), Nl, t["dX"].data_ptr(), Kl, t["dW"].data_ptr(), Nl))
+    axo.axo_layer_step_grouped(layers, None, 0, gu.stream())
+    torch.cuda.synchronize()
+    for i, (Xb, Wb, dYb, bias_b, epi, t) in enumerate(keep):
+        if Xb.shape[0] == 0:  # no tokens: dW is an empty sum
+            assert not gu.to_host(t["dW"]).any()
+            continue
+        tag = f"layer {i}"
+        gu.assert_close(oracle, gu.to_host(t["Y"]), oracle.fc_fwd(Xb, Wb, bias_b if epi else None, epi), tag + " fwd")
+        gu.assert_close(oracle, gu.to_host(t["dX"]), oracle.fc_dgrad(dYb, Wb), tag + " dgrad")
+        gu.assert_close(oracle, gu.to_host(t["dW"]), oracle.fc_wgrad(Xb, dYb), tag + " wgrad")
