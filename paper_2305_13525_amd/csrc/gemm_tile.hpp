@@ -280,11 +280,14 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     // to write LDS it puts a full vmcnt(0) wait in front of every later transposing LDS read,
     // which stalls the wave for a whole memory latency in every step.  The kernel keeps the
     // ordering itself: the vmcnt(0) wait and the barrier before the last MFMA group of each step.
+    // M0 is written here without being declared: it is a reserved register that the compiler
+    // never allocates and only sets itself right before instructions that read it (LDS-DMA and
+    // lane-indexed moves), none of which this kernel makes it generate.
     auto load_lds = [](uint32_t lds_dst, uint32_t off, u32x4_t rsrc, uint32_t soff) __attribute__((always_inline)) {
         asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                      :
                      : "s"(lds_dst), "v"(off), "s"(rsrc), "s"(soff)
-                     : "memory", "m0");
+                     : "memory");
     };
     // Loads LO..HI-1 of the NL loads that fill stage s with the step at (a_soff, b_soff): the A
     // rounds first, then the B rounds; round j of wave w lands at tile + (j * 512 + w * 64 + lane) * 16.

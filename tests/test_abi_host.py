@@ -2,6 +2,7 @@
 include/axo.h declares, derives shards the way Section 3.2 of the paper cuts I and W over the
 grid, and turns every malformed argument into its status code before any HIP call."""
 import ctypes
+import glob
 import os
 import re
 
@@ -18,16 +19,19 @@ OK, BAD_GRID, BAD_COORD, INDIVISIBLE, NULL_PTR, MISALIGNED, BAD_LD, WORKSPACE, B
 
 
 def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(axo_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for header in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))):
+        text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+        names |= set(re.findall(r"\b(axo_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"axo_fc_fwd", "axo_fc_dgrad", "axo_fc_wgrad", "axo_layer_step", "axo_shard_dims",
             "axo_workspace_bytes", "axo_status_string", "axo_version",
-            "axo_layer_step_workspace_bytes", "axo_layer_step_grouped"} <= set(names)
+            "axo_layer_step_workspace_bytes", "axo_layer_step_grouped", "axo_comm_rank_configs",
+            "axo_comm_layer_time"} <= set(names)
     lib = ctypes.CDLL(axo.library_path())
     for n in names:
         assert hasattr(lib, n), n
