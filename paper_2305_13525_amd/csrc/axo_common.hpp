@@ -60,9 +60,12 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 // GELU, tanh form: 0.5 v (1 + tanh(z)) = v * sigmoid(2 z), z = sqrt(2/pi) (v + 0.044715 v^3).
 // The sigmoid form has no cancellation for large negative v.
 __device__ __forceinline__ float gelu_tanh(float v) {
-    const float c = 0.7978845608028654f;
-    float z = c * (v + 0.044715f * v * v * v);
-    return v / (1.0f + __expf(-2.0f * z));
+    // -2 z log2(e) = v (k1 + k3 v^2); one exp2 and one reciprocal (1 ulp each: far inside the bf16
+    // rounding that follows; a true division would cost ten more instructions per element)
+    const float k1 = -2.0f * 0.7978845608028654f * 1.4426950408889634f;
+    const float k3 = k1 * 0.044715f;
+    const float t = v * __builtin_fmaf(k3, v * v, k1);
+    return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
 }
 
 // GELU, erf form: 0.5 v (1 + erf(v / sqrt 2)) = 0.5 v erfc(-v / sqrt 2)  (no cancellation).
