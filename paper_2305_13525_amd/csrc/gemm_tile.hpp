@@ -427,7 +427,10 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
         const int row = pass * ROWS_PER_PASS + lane / LANES_PER_ROW;
         const int ch = lane % LANES_PER_ROW;
         const u32x4 vdat = *reinterpret_cast<const u32x4*>(stage + row * C::EPI_STRIDE + ch * 16);
-        *reinterpret_cast<u32x4*>(Cw + (int64_t)row * g.ldc + ch * 8) = vdat;
+        // non-temporal: the output is not read again by this launch, and a workgroup cannot retire
+        // before its stores are acknowledged (measured: 4-6 % of a 32-step tile's time with
+        // ordinary stores, about half of that with streaming ones)
+        __builtin_nontemporal_store(vdat, reinterpret_cast<u32x4*>(Cw + (int64_t)row * g.ldc + ch * 8));
     }
 }
 
