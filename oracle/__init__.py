@@ -43,6 +43,11 @@ def lib() -> ctypes.CDLL:
         L.oracle_gelu_tanh.argtypes = [ctypes.c_double]
         L.oracle_gelu_tanh.restype = ctypes.c_double
         L.oracle_num_threads.restype = ctypes.c_int
+        for name in ("oracle_dgelu_erf", "oracle_dgelu_tanh"):
+            getattr(L, name).argtypes = [ctypes.c_double]
+            getattr(L, name).restype = ctypes.c_double
+        L.oracle_fc_dgrad_act.argtypes = [p, i64, p, i64, p, i64, ctypes.c_int, i64, i64, i64, p, i64, p]
+        L.oracle_bias_grad.argtypes = [p, i64, i64, i64, p]
         _lib = L
     return _lib
 
@@ -112,6 +117,38 @@ def fc_wgrad(X: np.ndarray, dY: np.ndarray, rows: Optional[Sequence[int]] = None
     out = np.empty((n_rows, Nl), dtype=np.float64)
     lib().oracle_fc_wgrad(X.ctypes.data, _ld(X), dY.ctypes.data, _ld(dY), M, Kl, Nl, rp, n_rows, out.ctypes.data)
     return out
+
+
+def fc_dgrad_act(dY: np.ndarray, W: np.ndarray, pre: np.ndarray, act: int,
+                 rows: Optional[Sequence[int]] = None) -> np.ndarray:
+    """(dY . W^T) * act'(pre) in fp64: the data gradient taken through the activation of the layer below."""
+    dY, W, pre = _u16(dY), _u16(W), _u16(pre)
+    M, Nl = dY.shape
+    Kl = W.shape[0]
+    assert W.shape[1] == Nl and pre.shape == (M, Kl)
+    keep, n_rows, rp = _rows(rows, M)
+    out = np.empty((n_rows, Kl), dtype=np.float64)
+    rc = lib().oracle_fc_dgrad_act(dY.ctypes.data, _ld(dY), W.ctypes.data, _ld(W), pre.ctypes.data, _ld(pre), int(act),
+                                   M, Kl, Nl, rp, n_rows, out.ctypes.data)
+    assert rc == 0
+    return out
+
+
+def bias_grad(dY: np.ndarray) -> np.ndarray:
+    """Column sums of dY in fp64: the bias gradient."""
+    dY = _u16(dY)
+    M, Nl = dY.shape
+    out = np.empty(Nl, dtype=np.float64)
+    lib().oracle_bias_grad(dY.ctypes.data, _ld(dY), M, Nl, out.ctypes.data)
+    return out
+
+
+def dgelu_tanh(x: float) -> float:
+    return float(lib().oracle_dgelu_tanh(float(x)))
+
+
+def dgelu_erf(x: float) -> float:
+    return float(lib().oracle_dgelu_erf(float(x)))
 
 
 def gelu_tanh(x: float) -> float:

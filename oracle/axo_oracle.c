@@ -20,6 +20,11 @@
  * is not in the paper; it is the usual GPT MLP epilogue and is evaluated in fp64
  * with libm on the fp64 sum.
  *
+ * The steps either side of the three products in a real layer (not in the paper's Algorithm 1,
+ * which stops at the products; Section 6.1 trains in mixed precision): the GELU derivative
+ * applied to the data gradient, the bias gradient (column sums of dO) and the accumulation of
+ * the weight gradient into an fp32 buffer are stated here too, in fp64.
+ *
  * Every routine takes an optional list of output rows, so that at full benchmark
  * sizes a sample of whole output rows can be computed one by one.
  *
@@ -68,6 +73,21 @@ double oracle_gelu_tanh(double x)
 {
     const double c = 0.79788456080286535588; /* sqrt(2/pi) */
     return 0.5 * x * (1.0 + tanh(c * (x + 0.044715 * x * x * x)));
+}
+
+/* d/dx of the exact GELU:  Phi(x) + x phi(x)  (phi, Phi: standard normal density and CDF). */
+double oracle_dgelu_erf(double x)
+{
+    const double phi = 0.39894228040143267794 * exp(-0.5 * x * x); /* 1/sqrt(2 pi) */
+    return 0.5 * (1.0 + erf(x * 0.70710678118654752440)) + x * phi;
+}
+
+/* d/dx of the tanh-form GELU: with u = c (x + a x^3), 0.5 (1 + tanh u) + 0.5 x (1 - tanh^2 u) c (1 + 3 a x^2). */
+double oracle_dgelu_tanh(double x)
+{
+    const double c = 0.79788456080286535588, a = 0.044715;
+    const double th = tanh(c * (x + a * x * x * x));
+    return 0.5 * (1.0 + th) + 0.5 * x * (1.0 - th * th) * c * (1.0 + 3.0 * a * x * x);
 }
 
 /* Forward local product (Algorithm 1, forward function, the local multiply).
@@ -119,6 +139,35 @@ int oracle_fc_dgrad(const uint16_t *dY, int64_t lddy, const uint16_t *W, int64_t
             out[r * Kl + k] = s;
         }
     }
+    return 0;
+}
+
+/* Data gradient through an activation: out[r, k] = (sum_n dY[t_r, n] W[k, n]) * act'(P[t_r, k]),
+ * P the bf16 pre-activation of the layer below; act: ORACLE_EPI_BIAS_GELU_TANH or _ERF. */
+int oracle_fc_dgrad_act(const uint16_t *dY, int64_t lddy, const uint16_t *W, int64_t ldw,
+                        const uint16_t *P, int64_t ldp, int act, int64_t M, int64_t Kl, int64_t Nl,
+                        const int64_t *rows, int64_t n_rows, double *out)
+{
+    if (act != ORACLE_EPI_BIAS_GELU_TANH && act != ORACLE_EPI_BIAS_GELU_ERF) return -1;
+    int rc = oracle_fc_dgrad(dY, lddy, W, ldw, M, Kl, Nl, rows, n_rows, out);
+    if (rc) return rc;
+    if (rows == NULL) n_rows = M;
+    for (int64_t r = 0; r < n_rows; ++r) {
+        const int64_t t = rows ? rows[r] : r;
+        for (int64_t k = 0; k < Kl; ++k) {
+            const double p = widen(P[t * ldp + k]);
+            out[r * Kl + k] *= act == ORACLE_EPI_BIAS_GELU_TANH ? oracle_dgelu_tanh(p) : oracle_dgelu_erf(p);
+        }
+    }
+    return 0;
+}
+
+/* Bias gradient: out[n] = sum_t dY[t, n]  (the column sums of dO), ascending t. */
+int oracle_bias_grad(const uint16_t *dY, int64_t lddy, int64_t M, int64_t Nl, double *out)
+{
+    for (int64_t n = 0; n < Nl; ++n) out[n] = 0.0;
+    for (int64_t t = 0; t < M; ++t)
+        for (int64_t n = 0; n < Nl; ++n) out[n] += widen(dY[t * lddy + n]);
     return 0;
 }
 
