@@ -131,6 +131,36 @@ int axo_fc_dgrad(const axo_problem_t *p, const void *dY, int64_t lddy, const voi
 int axo_fc_wgrad(const axo_problem_t *p, const void *X, int64_t ldx, const void *dY, int64_t lddy,
                  void *dW, int64_t lddw, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* ---- The steps either side of the three products in a layer's backward pass ------------------
+ * They are not part of the paper's Algorithm 1 (which stops at the products) but every layer of
+ * the networks it trains has them; mixed precision as in Section 6.1 (bf16 data, fp32 master
+ * gradients).  Like the forward epilogue they are applied to THIS GPU's partial result, which is
+ * the layer's true value only when the group that the product is reduced over has size 1. */
+
+/* Data gradient taken through the activation of the layer below:
+ *   dX[M x Kl] = (dY[M x Nl] . W[Kl x Nl]^T) * act'(pre[M x Kl]),
+ * pre = that layer's bf16 pre-activation (bias included), act = AXO_EPI_BIAS_GELU_TANH or
+ * AXO_EPI_BIAS_GELU_ERF (selects which GELU's derivative; no bias is involved).  The multiply
+ * happens on the fp32 accumulator, before the one rounding to bf16.  ldpre >= Kl; otherwise the
+ * rules of axo_fc_dgrad.  Errors: those of axo_fc_dgrad, BAD_EPILOGUE for any other act. */
+int axo_fc_dgrad_act(const axo_problem_t *p, const void *dY, int64_t lddy, const void *W, int64_t ldw,
+                     const void *pre, int64_t ldpre, int act, void *dX, int64_t lddx,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Weight gradient accumulated in fp32:  dW[Kl x Nl] += X[M x Kl]^T . dY[M x Nl], dW a device
+ * matrix of fp32 (the master gradient), lddw in fp32 elements, >= Nl and a multiple of 4, dW
+ * 16-byte aligned.  The product is added unrounded; each element is updated by exactly one
+ * workgroup, so the result does not depend on scheduling.  Otherwise the rules of axo_fc_wgrad. */
+int axo_fc_wgrad_acc(const axo_problem_t *p, const void *X, int64_t ldx, const void *dY, int64_t lddy,
+                     float *dW, int64_t lddw, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Bias gradient: db[n] = sum over the M local rows of dY[t, n] (accumulate == 0) or db[n] += that
+ * sum (accumulate == 1); db: Nl fp32 values in device memory, 4-byte aligned.  fp32 sums in a
+ * fixed order (no atomics).  Errors: problem errors, NULL_PTR, BAD_LD, MISALIGNED, BAD_ARG
+ * (accumulate not 0/1), HIP. */
+int axo_bias_grad(const axo_problem_t *p, const void *dY, int64_t lddy, float *db, int accumulate,
+                  void *hip_stream);
+
 /* One FC layer of a chain: its problem, epilogue, and the caller's buffers with their leading
  * dimensions.  X and W are kept by the caller between forward and backward (the cache of
  * Algorithm 1's forward function).  dY is the gradient with respect to the layer's output

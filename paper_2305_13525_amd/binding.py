@@ -86,6 +86,12 @@ def library() -> ctypes.CDLL:
     L.axo_layer_step_workspace_bytes.restype = sz
     L.axo_layer_step.argtypes = [ctypes.POINTER(Layer), i32, vp, sz, vp]
     L.axo_layer_step.restype = i32
+    L.axo_fc_dgrad_act.argtypes = [PP, vp, i64, vp, i64, vp, i64, i32, vp, i64, vp, sz, vp]
+    L.axo_fc_dgrad_act.restype = i32
+    L.axo_fc_wgrad_acc.argtypes = [PP, vp, i64, vp, i64, vp, i64, vp, sz, vp]
+    L.axo_fc_wgrad_acc.restype = i32
+    L.axo_bias_grad.argtypes = [PP, vp, i64, vp, i32, vp]
+    L.axo_bias_grad.restype = i32
     L.axo_layer_step_grouped.argtypes = [ctypes.POINTER(Layer), i32, vp, sz, vp]
     L.axo_layer_step_grouped.restype = i32
     _lib = L
@@ -161,3 +167,22 @@ def axo_layer_step_grouped(layers: Sequence[Layer], ws: Optional[int] = None, ws
                            stream: Optional[int] = None, check: bool = True) -> int:
     rc = library().axo_layer_step_grouped(_layer_array(layers), len(layers), ws, ws_bytes, stream)
     return _check(rc, "axo_layer_step_grouped", check)
+
+
+def axo_fc_dgrad_act(p: Problem, dY: int, lddy: int, W: int, ldw: int, pre: int, ldpre: int, act: int, dX: int,
+                     lddx: int, ws: Optional[int] = None, ws_bytes: int = 0, stream: Optional[int] = None,
+                     check: bool = True) -> int:
+    rc = library().axo_fc_dgrad_act(ctypes.byref(p), dY, lddy, W, ldw, pre, ldpre, act, dX, lddx, ws, ws_bytes, stream)
+    return _check(rc, "axo_fc_dgrad_act", check)
+
+
+def axo_fc_wgrad_acc(p: Problem, X: int, ldx: int, dY: int, lddy: int, dW: int, lddw: int, ws: Optional[int] = None,
+                     ws_bytes: int = 0, stream: Optional[int] = None, check: bool = True) -> int:
+    rc = library().axo_fc_wgrad_acc(ctypes.byref(p), X, ldx, dY, lddy, dW, lddw, ws, ws_bytes, stream)
+    return _check(rc, "axo_fc_wgrad_acc", check)
+
+
+def axo_bias_grad(p: Problem, dY: int, lddy: int, db: int, accumulate: int = 0, stream: Optional[int] = None,
+                  check: bool = True) -> int:
+    rc = library().axo_bias_grad(ctypes.byref(p), dY, lddy, db, accumulate, stream)
+    return _check(rc, "axo_bias_grad", check)

@@ -17,6 +17,7 @@
 #include <vector>
 
 #include "axo_common.hpp"
+#include "bias_grad.hpp"
 #include "gemm_generic.hpp"
 #include "gemm_tile.hpp"
 
@@ -330,6 +331,7 @@ int plan_fwd(const axo_problem_t* p, const void* X, int64_t ldx, const void* W, 
     g.B = static_cast<const axo::bf16_t*>(W); g.ldb = ldw;
     g.C = static_cast<axo::bf16_t*>(Y); g.ldc = ldy;
     g.bias = static_cast<const axo::bf16_t*>(bias);
+    g.aux = nullptr; g.ldaux = 0;
     g.Mo = (int)s.M; g.No = (int)s.Nl; g.R = (int)s.Kl;
     g.epilogue = epilogue;
     g.add_bias = (epilogue != AXO_EPI_NONE && s.k_coord == 0) ? 1 : 0;
@@ -351,6 +353,7 @@ int plan_dgrad(const axo_problem_t* p, const void* dY, int64_t lddy, const void*
     g.B = static_cast<const axo::bf16_t*>(W); g.ldb = ldw;
     g.C = static_cast<axo::bf16_t*>(dX); g.ldc = lddx;
     g.bias = nullptr;
+    g.aux = nullptr; g.ldaux = 0;
     g.Mo = (int)s.M; g.No = (int)s.Kl; g.R = (int)s.Nl;
     g.epilogue = AXO_EPI_NONE; g.add_bias = 0;
     out->la = axo::KC; out->lb = axo::KC;
@@ -371,6 +374,7 @@ int plan_wgrad(const axo_problem_t* p, const void* X, int64_t ldx, const void* d
     g.B = static_cast<const axo::bf16_t*>(dY); g.ldb = lddy;
     g.C = static_cast<axo::bf16_t*>(dW); g.ldc = lddw;
     g.bias = nullptr;
+    g.aux = nullptr; g.ldaux = 0;
     g.Mo = (int)s.Kl; g.No = (int)s.Nl; g.R = (int)s.M;
     g.epilogue = AXO_EPI_NONE; g.add_bias = 0;
     out->la = axo::MC; out->lb = axo::MC;
@@ -397,6 +401,39 @@ int plan_chain(const axo_layer_t* layers, int n_layers, void* ws, size_t ws_byte
         rc = plan_wgrad(&L.p, L.X, L.ldx, L.dY, L.lddy, L.dW, L.lddw, ws, ws_bytes, &(*out)[b + 1]);
         if (rc) return rc;
     }
+    return AXO_OK;
+}
+
+// dgrad with the activation's derivative fused in (see axo_fc_dgrad_act)
+int plan_dgrad_act(const axo_problem_t* p, const void* dY, int64_t lddy, const void* W, int64_t ldw, const void* pre,
+                   int64_t ldpre, int act, void* dX, int64_t lddx, void* ws, size_t ws_bytes, Plan* out) {
+    if (act != AXO_EPI_BIAS_GELU_TANH && act != AXO_EPI_BIAS_GELU_ERF) return AXO_ERR_BAD_EPILOGUE;
+    int rc = plan_dgrad(p, dY, lddy, W, ldw, dX, lddx, ws, ws_bytes, out);
+    if (rc) return rc;
+    if ((rc = check_matrix(pre, ldpre, out->g.Mo, out->g.No))) return rc;
+    out->g.aux = static_cast<const axo::bf16_t*>(pre);
+    out->g.ldaux = ldpre;
+    out->g.epilogue = act == AXO_EPI_BIAS_GELU_TANH ? axo::EPI_MUL_DGELU_TANH : axo::EPI_MUL_DGELU_ERF;
+    return AXO_OK;
+}
+
+// wgrad accumulated into an fp32 matrix (see axo_fc_wgrad_acc)
+int plan_wgrad_acc(const axo_problem_t* p, const void* X, int64_t ldx, const void* dY, int64_t lddy, float* dW32,
+                   int64_t lddw, void* ws, size_t ws_bytes, Plan* out) {
+    Shard s;
+    int rc = derive_shard(p, &s);
+    if (rc) return rc;
+    if (s.Kl > 0 && s.Nl > 0) {  // the fp32 output: 16-byte aligned rows of 4-byte elements
+        if (!dW32) return AXO_ERR_NULL_PTR;
+        if (lddw < s.Nl) return AXO_ERR_BAD_LD;
+        if (!aligned16(dW32) || (lddw % 4) != 0) return AXO_ERR_MISALIGNED;
+    }
+    // the bf16 checks of the output do not apply; validate the inputs through plan_wgrad with a stand-in
+    rc = plan_wgrad(p, X, ldx, dY, lddy, dW32, (lddw + 7) / 8 * 8, ws, ws_bytes, out);
+    if (rc) return rc;
+    out->g.C = reinterpret_cast<axo::bf16_t*>(dW32);
+    out->g.ldc = lddw;
+    out->g.epilogue = axo::EPI_ACC_F32;
     return AXO_OK;
 }
 
@@ -467,6 +504,43 @@ int axo_fc_wgrad(const axo_problem_t* p, const void* X, int64_t ldx, const void*
     int rc = plan_wgrad(p, X, ldx, dY, lddy, dW, lddw, ws, ws_bytes, &pl);
     if (rc) return rc;
     return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+}
+
+int axo_fc_dgrad_act(const axo_problem_t* p, const void* dY, int64_t lddy, const void* W, int64_t ldw, const void* pre,
+                     int64_t ldpre, int act, void* dX, int64_t lddx, void* ws, size_t ws_bytes, void* hip_stream) {
+    Plan pl;
+    int rc = plan_dgrad_act(p, dY, lddy, W, ldw, pre, ldpre, act, dX, lddx, ws, ws_bytes, &pl);
+    if (rc) return rc;
+    return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+}
+
+int axo_fc_wgrad_acc(const axo_problem_t* p, const void* X, int64_t ldx, const void* dY, int64_t lddy, float* dW,
+                     int64_t lddw, void* ws, size_t ws_bytes, void* hip_stream) {
+    Plan pl;
+    int rc = plan_wgrad_acc(p, X, ldx, dY, lddy, dW, lddw, ws, ws_bytes, &pl);
+    if (rc) return rc;
+    return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+}
+
+int axo_bias_grad(const axo_problem_t* p, const void* dY, int64_t lddy, float* db, int accumulate, void* hip_stream) {
+    Shard s;
+    int rc = derive_shard(p, &s);
+    if (rc) return rc;
+    if (accumulate != 0 && accumulate != 1) return AXO_ERR_BAD_ARG;
+    if ((rc = check_matrix(dY, lddy, s.M, s.Nl))) return rc;
+    if (s.Nl == 0) return AXO_OK;
+    if (!db) return AXO_ERR_NULL_PTR;
+    if (reinterpret_cast<uintptr_t>(db) & 3u) return AXO_ERR_MISALIGNED;
+    axo::BiasGradArgs g;
+    g.dY = static_cast<const axo::bf16_t*>(dY);
+    g.lddy = lddy;
+    g.db = db;
+    g.M = (int)s.M;
+    g.Nl = (int)s.Nl;
+    g.accumulate = accumulate;
+    const unsigned blocks = (unsigned)((s.Nl + axo::BG_COLS - 1) / axo::BG_COLS);
+    hipLaunchKernelGGL(axo::bias_grad_kernel, dim3(blocks), dim3(axo::BG_THREADS), 0, static_cast<hipStream_t>(hip_stream), g);
+    return hipGetLastError() == hipSuccess ? AXO_OK : AXO_ERR_HIP;
 }
 
 size_t axo_layer_step_workspace_bytes(const axo_layer_t* layers, int n_layers) {

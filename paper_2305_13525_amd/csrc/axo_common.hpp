@@ -21,14 +21,21 @@ typedef uint16_t bf16_t;  // bf16 bit pattern in memory
 //   MC: the output index i (or j) is contiguous         (element (i,r) at r*ld + i)
 enum Layout { KC = 0, MC = 1 };
 
-enum Epilogue { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_GELU_TANH = 2, EPI_BIAS_GELU_ERF = 3 };
+// What happens to the fp32 accumulator on its way out.  1-3 belong to the forward product, 4-5
+// to dgrad (multiply by the activation's derivative at the pre-activation `aux`), 6 to wgrad
+// (add into an fp32 matrix instead of rounding to bf16).
+enum Epilogue {
+    EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_GELU_TANH = 2, EPI_BIAS_GELU_ERF = 3,
+    EPI_MUL_DGELU_TANH = 4, EPI_MUL_DGELU_ERF = 5, EPI_ACC_F32 = 6
+};
 
 // One GEMM as the kernels see it.
 struct GemmArgs {
     const bf16_t* A; int64_t lda;
     const bf16_t* B; int64_t ldb;
-    bf16_t* C;       int64_t ldc;
+    bf16_t* C;       int64_t ldc;   // EPI_ACC_F32: C points to fp32 and ldc counts fp32 elements
     const bf16_t* bias;  // [No] or nullptr
+    const bf16_t* aux; int64_t ldaux;  // [Mo x No] pre-activation for EPI_MUL_DGELU_*, else nullptr
     int Mo, No, R;       // output rows, output cols, reduction length
     int epilogue;        // Epilogue
     int add_bias;        // 0: bias pointer ignored (shard is not at K-coordinate 0)
@@ -73,11 +80,33 @@ __device__ __forceinline__ float gelu_erf(float v) {
     return 0.5f * v * erfcf(-v * 0.7071067811865475f);
 }
 
+// d/dv of the tanh-form GELU.  With s = sigmoid(2 z): 0.5 (1 + tanh z) = s and 1 - tanh^2 z = 4 s (1 - s),
+// so the derivative is s (1 + 2 v (1 - s) z'), z' = sqrt(2/pi) (1 + 3 * 0.044715 v^2).
+__device__ __forceinline__ float dgelu_tanh(float v) {
+    const float c = 0.7978845608028654f;
+    const float k1 = -2.0f * c * 1.4426950408889634f, k3 = k1 * 0.044715f;
+    const float v2 = v * v;
+    const float s = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(v * __builtin_fmaf(k3, v2, k1)));
+    const float dz = c * __builtin_fmaf(3.0f * 0.044715f, v2, 1.0f);
+    return s * __builtin_fmaf(2.0f * v * (1.0f - s), dz, 1.0f);
+}
+
+// d/dv of the exact GELU: Phi(v) + v phi(v).
+__device__ __forceinline__ float dgelu_erf(float v) {
+    const float phi = 0.3989422804014327f * __expf(-0.5f * v * v);
+    return 0.5f * erfcf(-v * 0.7071067811865475f) + v * phi;
+}
+
 __device__ __forceinline__ float apply_epilogue(float acc, float b, int epi) {
     float v = acc + b;
     if (epi == EPI_BIAS_GELU_TANH) v = gelu_tanh(v);
     else if (epi == EPI_BIAS_GELU_ERF) v = gelu_erf(v);
     return v;
+}
+
+// dgrad through an activation: accumulator times the activation's derivative at pre-activation p
+__device__ __forceinline__ float apply_dact(float acc, float p, int epi) {
+    return acc * (epi == EPI_MUL_DGELU_TANH ? dgelu_tanh(p) : dgelu_erf(p));
 }
 
 }  // namespace axo

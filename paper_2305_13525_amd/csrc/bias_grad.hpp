@@ -1,0 +1,63 @@
+// Bias gradient: db[n] (+)= sum_t dY[t, n], dY bf16 row-major [M x Nl], db fp32.  Memory bound:
+// it reads dY once (2 M Nl bytes) and writes Nl floats.
+//
+// One 256-thread workgroup owns 32 columns: 4 lanes across (8 columns = one 16-byte load each)
+// by 64 lanes down the rows.  Every thread sums its rows t = r, r + 64, ... in fp32, the 64
+// partial sums of a column are added in a fixed tree through LDS, and lane (0, c) writes the
+// result: no atomics, so the result does not depend on scheduling.  32 columns per workgroup
+// (64-byte row segments) rather than 64 keeps the grid large enough to pull bandwidth from all
+// XCDs at layer widths of a few thousand columns.
+#pragma once
+#include "axo_common.hpp"
+
+namespace axo {
+
+constexpr int BG_COLS = 32, BG_THREADS = 256;
+
+struct BiasGradArgs {
+    const bf16_t* dY; int64_t lddy;
+    float* db;
+    int M, Nl;
+    int accumulate;  // 0: db = sums, 1: db += sums
+};
+
+__global__ void __launch_bounds__(BG_THREADS) bias_grad_kernel(BiasGradArgs g) {
+    __shared__ float part[64][BG_COLS + 1];
+    const int cx = threadIdx.x & 3, ry = threadIdx.x >> 2;
+    const int col = blockIdx.x * BG_COLS + cx * 8;
+    const int valid = g.Nl - col;  // columns of this thread's chunk inside the matrix (may be <= 0 or >= 8)
+    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (valid >= 8) {
+        for (int t = ry; t < g.M; t += 64) {
+            const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(g.dY + (int64_t)t * g.lddy + col));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                s[2 * i] += __uint_as_float(w[i] << 16);
+                s[2 * i + 1] += __uint_as_float(w[i] & 0xFFFF0000u);
+            }
+        }
+    } else if (valid > 0) {  // ragged last chunk
+        for (int t = ry; t < g.M; t += 64)
+            for (int i = 0; i < valid; ++i) s[i] += bf16_bits_to_f32(g.dY[(int64_t)t * g.lddy + col + i]);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) part[ry][cx * 8 + i] = s[i];
+    __syncthreads();
+    for (int half = 32; half >= 1; half >>= 1) {  // fixed-shape tree over the 64 row lanes
+        if (ry < half) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) part[ry][cx * 8 + i] += part[ry + half][cx * 8 + i];
+        }
+        __syncthreads();
+    }
+    if (ry == 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (col + i < g.Nl) {
+                const float v = part[0][cx * 8 + i];
+                g.db[col + i] = g.accumulate ? g.db[col + i] + v : v;
+            }
+    }
+}
+
+}  // namespace axo

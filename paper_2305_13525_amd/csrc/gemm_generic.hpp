@@ -115,13 +115,20 @@ __global__ void __launch_bounds__(256) gemm_generic_kernel(GemmArgs g) {
             const int col = j0 + wn * 64 + b * 32 + (lane & 31);
             if (col >= g.No) continue;
             float bv = 0.0f;
-            if (g.epilogue != EPI_NONE && g.add_bias) bv = bf16_bits_to_f32(g.bias[col]);
+            if (g.epilogue >= EPI_BIAS && g.epilogue <= EPI_BIAS_GELU_ERF && g.add_bias) bv = bf16_bits_to_f32(g.bias[col]);
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int row = i0 + wm * 64 + a * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
                 if (row < g.Mo) {
                     float v = acc[a][b][e];
-                    if (g.epilogue != EPI_NONE) v = apply_epilogue(v, bv, g.epilogue);
+                    if (g.epilogue == EPI_ACC_F32) {
+                        reinterpret_cast<float*>(g.C)[(int64_t)row * g.ldc + col] += v;
+                        continue;
+                    }
+                    if (g.epilogue == EPI_MUL_DGELU_TANH || g.epilogue == EPI_MUL_DGELU_ERF)
+                        v = apply_dact(v, bf16_bits_to_f32(g.aux[(int64_t)row * g.ldaux + col]), g.epilogue);
+                    else if (g.epilogue != EPI_NONE)
+                        v = apply_epilogue(v, bv, g.epilogue);
                     g.C[(int64_t)row * g.ldc + col] = f32_to_bf16_bits(v);
                 }
             }

@@ -381,14 +381,22 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     // the epilogue kind is decided once, outside the element loops: the plain path is then
     // straight-line code (the activation code is large; branching around it per element made the
     // epilogue several times slower than the stores it feeds)
+    // Origin of the wave tile in the output.  Pinned in scalar registers ahead of the epilogue
+    // switch: when the compiler was left to rematerialise these sums inside each branch, one
+    // branch of the three-way dgrad switch came out without the column term (it stayed undefined
+    // on that path in the generated code) and the stores that follow the switch went astray.
+    int wrow0 = i0 + wm * C::WTM, wcol0 = j0 + wn * C::WTN;
+    asm volatile("" : "+s"(wrow0), "+s"(wcol0));
     auto convert_and_stage = [&](auto epi_tag) __attribute__((always_inline)) {
         constexpr int EPI = decltype(epi_tag)::value;
+        constexpr bool FWD_EPI = EPI >= EPI_BIAS && EPI <= EPI_BIAS_GELU_ERF;
+        constexpr bool DACT = EPI == EPI_MUL_DGELU_TANH || EPI == EPI_MUL_DGELU_ERF;
 #pragma unroll
         for (int b = 0; b < C::TN; ++b) {
             const int ncol = b * 16 + 4 * (lane >> 4);  // within the wave tile
             float bv[4] = {0.f, 0.f, 0.f, 0.f};
-            if (EPI != EPI_NONE && g.add_bias) {
-                const uint2 raw = *reinterpret_cast<const uint2*>(g.bias + j0 + wn * C::WTN + ncol);
+            if (FWD_EPI && g.add_bias) {
+                const uint2 raw = *reinterpret_cast<const uint2*>(g.bias + wcol0 + ncol);
                 bv[0] = __uint_as_float(raw.x << 16);
                 bv[1] = __uint_as_float(raw.x & 0xFFFF0000u);
                 bv[2] = __uint_as_float(raw.y << 16);
@@ -396,32 +404,65 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
             }
 #pragma unroll
             for (int a = 0; a < C::TM; ++a) {
+                const int mrow = a * 16 + (lane & 15);
                 float v[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    v[e] = acc[a][b][e];
-                    if (EPI != EPI_NONE) v[e] = apply_epilogue(v[e], bv[e], EPI);
+                for (int e = 0; e < 4; ++e) v[e] = acc[a][b][e];
+                if (FWD_EPI) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = apply_epilogue(v[e], bv[e], EPI);
+                }
+                if (DACT) {  // the four pre-activations that belong to this lane's four outputs
+                    const uint2 raw = *reinterpret_cast<const uint2*>(
+                        g.aux + (int64_t)(wrow0 + mrow) * g.ldaux + wcol0 + ncol);
+                    v[0] = apply_dact(v[0], __uint_as_float(raw.x << 16), EPI);
+                    v[1] = apply_dact(v[1], __uint_as_float(raw.x & 0xFFFF0000u), EPI);
+                    v[2] = apply_dact(v[2], __uint_as_float(raw.y << 16), EPI);
+                    v[3] = apply_dact(v[3], __uint_as_float(raw.y & 0xFFFF0000u), EPI);
                 }
                 uint2 packed;
                 packed.x = pack_bf16x2(v[0], v[1]);
                 packed.y = pack_bf16x2(v[2], v[3]);
-                const int mrow = a * 16 + (lane & 15);
                 *reinterpret_cast<uint2*>(stage + mrow * C::EPI_STRIDE + ncol * 2) = packed;
             }
         }
     };
-    switch (g.epilogue) {
-        case EPI_NONE: convert_and_stage(std::integral_constant<int, EPI_NONE>{}); break;
-        case EPI_BIAS: convert_and_stage(std::integral_constant<int, EPI_BIAS>{}); break;
-        case EPI_BIAS_GELU_TANH: convert_and_stage(std::integral_constant<int, EPI_BIAS_GELU_TANH>{}); break;
-        default: convert_and_stage(std::integral_constant<int, EPI_BIAS_GELU_ERF>{}); break;
+    // Each product has its own epilogue kinds, so each layout pair compiles only those.
+    if (LA == KC && LB == MC) {  // forward
+        switch (g.epilogue) {
+            case EPI_NONE: convert_and_stage(IC<EPI_NONE>{}); break;
+            case EPI_BIAS: convert_and_stage(IC<EPI_BIAS>{}); break;
+            case EPI_BIAS_GELU_TANH: convert_and_stage(IC<EPI_BIAS_GELU_TANH>{}); break;
+            default: convert_and_stage(IC<EPI_BIAS_GELU_ERF>{}); break;
+        }
+    } else if (LA == KC && LB == KC) {  // dgrad
+        switch (g.epilogue) {
+            case EPI_NONE: convert_and_stage(IC<EPI_NONE>{}); break;
+            case EPI_MUL_DGELU_TANH: convert_and_stage(IC<EPI_MUL_DGELU_TANH>{}); break;
+            default: convert_and_stage(IC<EPI_MUL_DGELU_ERF>{}); break;
+        }
+    } else {  // wgrad
+        if (g.epilogue == EPI_ACC_F32) {
+            // fp32 accumulation, straight from the registers: a lane's 4 columns are 16 bytes, the
+            // four 16-lane groups make a 64-byte run per row; read, add, write back, no rounding
+            float* Cf = reinterpret_cast<float*>(g.C) + (int64_t)wrow0 * g.ldc + wcol0;
+#pragma unroll
+            for (int a = 0; a < C::TM; ++a)
+#pragma unroll
+                for (int b = 0; b < C::TN; ++b) {
+                    f32x4* dst = reinterpret_cast<f32x4*>(Cf + (int64_t)(a * 16 + (lane & 15)) * g.ldc + b * 16 + 4 * (lane >> 4));
+                    *dst = *dst + acc[a][b];
+                }
+            return;
+        }
+        convert_and_stage(IC<EPI_NONE>{});
     }
     // the staging region is private to the wave: only wave-level ordering is needed
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
     __builtin_amdgcn_wave_barrier();
     constexpr int LANES_PER_ROW = C::WTN * 2 / 16;
     constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
-    bf16_t* Cw = g.C + (int64_t)(i0 + wm * C::WTM) * g.ldc + j0 + wn * C::WTN;
+    bf16_t* Cw = g.C + (int64_t)wrow0 * g.ldc + wcol0;
 #pragma unroll
     for (int pass = 0; pass < C::WTM / ROWS_PER_PASS; ++pass) {
         const int row = pass * ROWS_PER_PASS + lane / LANES_PER_ROW;

@@ -177,3 +177,29 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(b, "_LIB_PATH", "/nonexistent/libaxo.so")
     with pytest.raises(FileNotFoundError):
         b.library()
+
+
+def test_backward_extras_argument_errors():
+    p = axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 48)
+    # dgrad through an activation: act must name one of the two GELUs; pre is a [M x Kl] matrix
+    assert axo.axo_fc_dgrad_act(p, A, 48, A, 48, A, 32, 1, A, 32, check=False) == BAD_EPI
+    assert axo.axo_fc_dgrad_act(p, A, 48, A, 48, None, 32, 2, A, 32, check=False) == NULL_PTR
+    assert axo.axo_fc_dgrad_act(p, A, 48, A, 48, A, 24, 3, A, 32, check=False) == BAD_LD
+    assert axo.axo_fc_dgrad_act(p, A, 40, A, 48, A, 32, 2, A, 32, check=False) == BAD_LD
+    # fp32 accumulation: ld in floats, multiple of 4, 16-byte aligned base
+    assert axo.axo_fc_wgrad_acc(p, A, 32, A, 48, None, 48, check=False) == NULL_PTR
+    assert axo.axo_fc_wgrad_acc(p, A, 32, A, 48, A, 40, check=False) == BAD_LD
+    assert axo.axo_fc_wgrad_acc(p, A, 32, A, 48, A, 50, check=False) == MISALIGNED
+    assert axo.axo_fc_wgrad_acc(p, A, 32, A, 48, A + 8, 48, check=False) == MISALIGNED
+    assert axo.axo_fc_wgrad_acc(p, A, 24, A, 48, A, 48, check=False) == BAD_LD
+    # bias gradient
+    assert axo.axo_bias_grad(p, A, 48, None, 0, check=False) == NULL_PTR
+    assert axo.axo_bias_grad(p, A, 48, A + 2, 0, check=False) == MISALIGNED
+    assert axo.axo_bias_grad(p, A, 48, A, 2, check=False) == BAD_ARG
+    assert axo.axo_bias_grad(p, A, 40, A, 0, check=False) == BAD_LD
+    # nothing to do: valid without a device
+    pn = axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 0)
+    assert axo.axo_bias_grad(pn, A, 8, A, 0, check=False) == OK
+    assert axo.axo_fc_wgrad_acc(pn, A, 32, A, 8, A, 8, check=False) == OK
+    p0 = axo.Problem.make((1, 1, 1), (0, 0, 0), 0, 32, 48)
+    assert axo.axo_fc_dgrad_act(p0, A, 48, A, 48, A, 32, 2, A, 32, check=False) == OK

@@ -1,0 +1,116 @@
+"""GPU parity of the backward-side extras against the fp64 oracle: dgrad with the GELU derivative
+fused in, wgrad accumulated into an fp32 matrix, and the bias gradient.  Same tolerances as the
+products for the bf16 output; the fp32 outputs are held to fp32 summation error."""
+import numpy as np
+import pytest
+
+import axo_synth as syn
+import oracle
+import paper_2305_13525_amd as axo
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import gpu_util as gu  # noqa: E402
+
+SHAPES = [(256, 256, 256), (512, 384, 640), (300, 72, 136), (1024, 128, 1280), (77, 40, 24), (768, 256, 1152)]
+
+
+def P(M, Kl, Nl):
+    return axo.Problem.make((1, 1, 1), (0, 0, 0), M, Kl, Nl)
+
+
+@pytest.mark.parametrize("act", [axo.AXO_EPI_BIAS_GELU_TANH, axo.AXO_EPI_BIAS_GELU_ERF])
+@pytest.mark.parametrize("M,Kl,Nl", SHAPES)
+def test_dgrad_through_gelu(M, Kl, Nl, act):
+    dYb, Wb = syn.normal_bf16(21, 0, (M, Nl), 1.0), syn.normal_bf16(21, 1, (Kl, Nl), 0.05)
+    Pb = syn.normal_bf16(21, 2, (M, Kl), 1.5)      # pre-activations on both sides of the GELU's bend
+    dY, W, pre, dX = gu.to_dev(dYb), gu.to_dev(Wb), gu.to_dev(Pb), gu.empty_dev(M, Kl)
+    axo.axo_fc_dgrad_act(P(M, Kl, Nl), dY.data_ptr(), Nl, W.data_ptr(), Nl, pre.data_ptr(), Kl, act, dX.data_ptr(), Kl,
+                         None, 0, gu.stream())
+    torch.cuda.synchronize()
+    gu.assert_close(oracle, gu.to_host(dX), oracle.fc_dgrad_act(dYb, Wb, Pb, act), f"dgrad_act {act}")
+
+
+def test_dgrad_through_gelu_in_place_shard():
+    """Shard of a (2,2,2) grid addressed inside the global tensors (leading dimensions > row length)."""
+    T, K, N, grid, c = 512, 512, 1024, (2, 2, 2), (1, 0, 1)
+    dYg, Wg, Pg = syn.normal_bf16(22, 0, (T, N), 1.0), syn.normal_bf16(22, 1, (K, N), 0.05), syn.normal_bf16(22, 2, (T, K), 1.5)
+    p = axo.Problem.make(grid, c, T, K, N)
+    _, (M, Kl, Nl, r0, k0, n0) = axo.axo_shard_dims(p)
+    dY, W, pre, dX = gu.to_dev(dYg), gu.to_dev(Wg), gu.to_dev(Pg), gu.empty_dev(T, K)
+    axo.axo_fc_dgrad_act(p, dY[r0:, n0:].data_ptr(), N, W[k0:, n0:].data_ptr(), N, pre[r0:, k0:].data_ptr(), K,
+                         axo.AXO_EPI_BIAS_GELU_TANH, dX[r0:, k0:].data_ptr(), K, None, 0, gu.stream())
+    torch.cuda.synchronize()
+    ref = oracle.fc_dgrad_act(dYg[r0:r0 + M, n0:n0 + Nl], Wg[k0:k0 + Kl, n0:n0 + Nl], Pg[r0:r0 + M, k0:k0 + Kl],
+                              oracle.EPI_BIAS_GELU_TANH)
+    out = gu.to_host(dX)
+    gu.assert_close(oracle, out[r0:r0 + M, k0:k0 + Kl], ref, "in-place dgrad_act")
+    mask = np.ones((T, K), dtype=bool)
+    mask[r0:r0 + M, k0:k0 + Kl] = False
+    assert (out[mask] == 0x7FC0).all()          # nothing outside the shard was written
+
+
+@pytest.mark.parametrize("M,Kl,Nl", SHAPES)
+def test_wgrad_accumulates_in_fp32(M, Kl, Nl):
+    Xb, dYb = syn.normal_bf16(23, 0, (M, Kl), 1.0), syn.normal_bf16(23, 1, (M, Nl), 1.0)
+    base = (np.random.default_rng(23).standard_normal((Kl, Nl)) * 30.0).astype(np.float32)
+    X, dY = gu.to_dev(Xb), gu.to_dev(dYb)
+    dW = torch.from_numpy(base.copy()).to("cuda:0")
+    p = P(M, Kl, Nl)
+    ref = oracle.fc_wgrad(Xb, dYb)
+    scale = np.sqrt(M)                           # typical magnitude of one sum of M products of unit normals
+    for rep in (1, 2):                           # accumulate twice: base + product, then + product again
+        axo.axo_fc_wgrad_acc(p, X.data_ptr(), Kl, dY.data_ptr(), Nl, dW.data_ptr(), Nl, None, 0, gu.stream())
+        torch.cuda.synchronize()
+        got = dW.cpu().numpy().astype(np.float64)
+        want = base.astype(np.float64) + rep * ref
+        # fp32 accumulation of M products plus the fp32 additions into the buffer: a few ulp of the sum's scale
+        assert np.max(np.abs(got - want)) <= 2e-5 * (scale + 30.0) * rep, (rep, np.max(np.abs(got - want)))
+
+
+def test_wgrad_acc_is_unrounded():
+    """The product is added without a bf16 rounding: small against large must survive."""
+    M, Kl, Nl = 256, 256, 256
+    Xb = syn.f32_to_bf16_bits(np.full((M, Kl), 2.0 ** -6, dtype=np.float32))
+    dYb = syn.f32_to_bf16_bits(np.full((M, Nl), 2.0 ** -6, dtype=np.float32))
+    dW = torch.full((Kl, Nl), 1024.0, dtype=torch.float32, device="cuda:0")
+    axo.axo_fc_wgrad_acc(P(M, Kl, Nl), gu.to_dev(Xb).data_ptr(), Kl, gu.to_dev(dYb).data_ptr(), Nl, dW.data_ptr(), Nl,
+                         None, 0, gu.stream())
+    torch.cuda.synchronize()
+    # 256 * 2^-12 = 2^-4 added to 1024: exactly representable in fp32, lost entirely in bf16
+    assert torch.all(dW == 1024.0 + 2.0 ** -4)
+
+
+@pytest.mark.parametrize("M,Nl", [(256, 256), (4096, 1536), (300, 136), (77, 24), (1, 8), (1000, 40), (513, 4104)])
+def test_bias_grad(M, Nl):
+    dYb = syn.normal_bf16(24, 0, (M, Nl), 1.0)
+    dY = gu.to_dev(dYb)
+    db = torch.full((Nl,), float("nan"), dtype=torch.float32, device="cuda:0")
+    p = P(M, 8, Nl)
+    axo.axo_bias_grad(p, dY.data_ptr(), Nl, db.data_ptr(), 0, gu.stream())
+    torch.cuda.synchronize()
+    ref = oracle.bias_grad(dYb)
+    tol = 4e-6 * np.sqrt(M) * 4 + 1e-6           # fp32 sums of M values of unit scale
+    got = db.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got - ref)) <= tol, np.max(np.abs(got - ref))
+    axo.axo_bias_grad(p, dY.data_ptr(), Nl, db.data_ptr(), 1, gu.stream())   # accumulate on top
+    torch.cuda.synchronize()
+    assert np.max(np.abs(db.cpu().numpy().astype(np.float64) - 2 * ref)) <= 2 * tol
+    # run-to-run identical (fixed summation order, no atomics)
+    db2 = torch.zeros_like(db)
+    axo.axo_bias_grad(p, dY.data_ptr(), Nl, db2.data_ptr(), 0, gu.stream())
+    db3 = torch.zeros_like(db)
+    axo.axo_bias_grad(p, dY.data_ptr(), Nl, db3.data_ptr(), 0, gu.stream())
+    torch.cuda.synchronize()
+    assert torch.equal(db2, db3)
+
+
+def test_bias_grad_in_place_columns():
+    M, N = 384, 1024
+    dYb = syn.normal_bf16(25, 0, (M, N), 1.0)
+    dY = gu.to_dev(dYb)
+    db = torch.zeros(256, dtype=torch.float32, device="cuda:0")
+    axo.axo_bias_grad(axo.Problem.make((1, 4, 1), (0, 2, 0), M, 8, N), dY[:, 512:].data_ptr(), N, db.data_ptr(), 0, gu.stream())
+    torch.cuda.synchronize()
+    assert np.max(np.abs(db.cpu().numpy() - oracle.bias_grad(dYb[:, 512:768]))) <= 1e-3
