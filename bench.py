@@ -45,6 +45,9 @@ def main() -> int:
                     help="entry point of the timed step: axo_layer_step_grouped (one launch over the tiles of all "
                          "products; the default) or axo_layer_step (one launch per product, in order)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the backward-side extras on the largest layer: dgrad through GELU, fp32-accumulating "
+                         "wgrad, bias gradient (reported under 'extras')")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE readings)")
     args = ap.parse_args()
@@ -174,6 +177,29 @@ def main() -> int:
                {"name": L.name, "grid": list(L.grid), "shard_MKN": list(L.shard), "epilogue": L.epilogue}
                for L in layers], "flop_per_step": flop},
            "roofline": roofline}
+
+    if args.extras:
+        L, o = layers[li], objs[li]
+        M, Kl, Nl = L.shard
+        pre = torch.randn((M, Kl), device="cuda:0").to(torch.bfloat16).view(torch.int16)
+        dW32 = torch.zeros((Kl, Nl), dtype=torch.float32, device="cuda:0")
+        db = torch.zeros((Nl,), dtype=torch.float32, device="cuda:0")
+        t_da = time_op(lambda: axo.axo_fc_dgrad_act(o.p, o.dY, o.lddy, o.W, o.ldw, pre.data_ptr(), Kl,
+                                                    axo.AXO_EPI_BIAS_GELU_TANH, o.dX, o.lddx, wsp, nws, st),
+                       args.steps, args.warmup)
+        t_wa = time_op(lambda: axo.axo_fc_wgrad_acc(o.p, o.X, o.ldx, o.dY, o.lddy, dW32.data_ptr(), Nl, wsp, nws, st),
+                       args.steps, args.warmup)
+        t_bg = time_op(lambda: axo.axo_bias_grad(o.p, o.dY, o.lddy, db.data_ptr(), 0, st), args.steps, args.warmup)
+        bg_bytes = 2 * M * Nl + 4 * Nl
+        out["extras"] = {
+            "layer": L.name,
+            "dgrad_gelu_tanh": {"ms": round(t_da, 5), "tflops": round(gflop / (t_da * 1e-3) / 1e12, 2),
+                                "plain_dgrad_ms": round(ops["dgrad"], 5)},
+            "wgrad_acc_f32": {"ms": round(t_wa, 5), "tflops": round(gflop / (t_wa * 1e-3) / 1e12, 2),
+                              "plain_wgrad_ms": round(ops["wgrad"], 5)},
+            "bias_grad": {"ms": round(t_bg, 5), "bound": "hbm", "algorithmic_bytes": bg_bytes,
+                          "achieved_GBps": round(bg_bytes / (t_bg * 1e-3) / 1e9, 1), "peak_GBps": 8000.0,
+                          "frac": round(bg_bytes / (t_bg * 1e-3) / 1e9 / 8000.0, 4)}}
 
     if args.all_configs:
         extra = {}
