@@ -463,15 +463,27 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     constexpr int LANES_PER_ROW = C::WTN * 2 / 16;
     constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
     bf16_t* Cw = g.C + (int64_t)wrow0 * g.ldc + wcol0;
+    // All reads of a batch are issued before its first store: interleaved one by one (as the
+    // compiler orders them when left alone) every store waits for its own LDS read, and the 16
+    // round trips cost more than the stores themselves (measured 5000 cycles for the slower wave
+    // of each SIMD).  The accumulators are dead by now, so the registers are free.
+    constexpr int PASSES = C::WTM / ROWS_PER_PASS, BATCH = 8;
+    static_assert(PASSES % BATCH == 0, "whole batches");
 #pragma unroll
-    for (int pass = 0; pass < C::WTM / ROWS_PER_PASS; ++pass) {
-        const int row = pass * ROWS_PER_PASS + lane / LANES_PER_ROW;
-        const int ch = lane % LANES_PER_ROW;
-        const u32x4 vdat = *reinterpret_cast<const u32x4*>(stage + row * C::EPI_STRIDE + ch * 16);
-        // non-temporal: the output is not read again by this launch, and a workgroup cannot retire
-        // before its stores are acknowledged (measured: 4-6 % of a 32-step tile's time with
-        // ordinary stores, about half of that with streaming ones)
-        __builtin_nontemporal_store(vdat, reinterpret_cast<u32x4*>(Cw + (int64_t)row * g.ldc + ch * 8));
+    for (int p0 = 0; p0 < PASSES; p0 += BATCH) {
+        u32x4 vdat[BATCH];
+#pragma unroll
+        for (int p = 0; p < BATCH; ++p) {
+            const int row = (p0 + p) * ROWS_PER_PASS + lane / LANES_PER_ROW, ch = lane % LANES_PER_ROW;
+            vdat[p] = *reinterpret_cast<const u32x4*>(stage + row * C::EPI_STRIDE + ch * 16);
+        }
+#pragma unroll
+        for (int p = 0; p < BATCH; ++p) {
+            const int row = (p0 + p) * ROWS_PER_PASS + lane / LANES_PER_ROW, ch = lane % LANES_PER_ROW;
+            // non-temporal: the output is not read again by this launch, and a workgroup cannot retire
+            // before its stores are acknowledged
+            __builtin_nontemporal_store(vdat[p], reinterpret_cast<u32x4*>(Cw + (int64_t)row * g.ldc + ch * 8));
+        }
     }
 }
 
