@@ -467,7 +467,7 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     // compiler orders them when left alone) every store waits for its own LDS read, and the 16
     // round trips cost more than the stores themselves (measured 5000 cycles for the slower wave
     // of each SIMD).  The accumulators are dead by now, so the registers are free.
-    constexpr int PASSES = C::WTM / ROWS_PER_PASS, BATCH = 8;
+    constexpr int PASSES = C::WTM / ROWS_PER_PASS, BATCH = PASSES;
     static_assert(PASSES % BATCH == 0, "whole batches");
 #pragma unroll
     for (int p0 = 0; p0 < PASSES; p0 += BATCH) {
