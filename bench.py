@@ -26,10 +26,10 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
 # (2.000 KiB per FETCH_SIZE count, 1.000 KiB per WRITE_SIZE count).  Keyed by (workload, product);
 # "group" is the single launch of the grouped step.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg2", "fwd"): int((82587.28 * 2.0 + 49152.0) * 1024),
-    ("cfg2", "dgrad"): int((98375.23 * 2.0 + 16384.0) * 1024),
-    ("cfg2", "wgrad"): int((82019.37 * 2.0 + 24576.0) * 1024),
-    ("cfg2", "group"): int((309812.07 * 2.0 + 90112.0) * 1024),
+    ("cfg2", "fwd"): int((82047.12 * 2.0 + 49171.62) * 1024),
+    ("cfg2", "dgrad"): int((98366.64 * 2.0 + 16387.68) * 1024),
+    ("cfg2", "wgrad"): int((82011.64 * 2.0 + 24580.39) * 1024),
+    ("cfg2", "group"): int((306171.62 * 2.0 + 90119.30) * 1024),
 }
 
 
