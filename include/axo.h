@@ -181,10 +181,13 @@ typedef struct axo_layer {
 /* Host only.  Largest workspace any single product of the chain needs. */
 size_t axo_layer_step_workspace_bytes(const axo_layer_t *layers, int n_layers);
 
-/* Forward of layers 0..n-1, then for layers n-1..0 the backward pair in the order dgrad, wgrad
- * (Section 4.1 issues the dgrad all-reduce before computing wgrad, which fixes this order), all
- * enqueued on one stream without host synchronisation.  All layers are validated before the
- * first launch; on a validation error nothing is enqueued. */
+/* Forward of layers 0..n-1, then for layers n-1..0 the backward pair dgrad, wgrad (Section 4.1
+ * issues the dgrad all-reduce before computing wgrad, which fixes this order), all enqueued on one
+ * stream without host synchronisation.  The forwards run one after the other, so a layer's Y may
+ * be the next layer's X; so do the backward pairs, so a layer's dX may be the previous layer's dY.
+ * Inside a pair the two products do not depend on each other (no output of a layer may overlap an
+ * input of the same layer) and may share one launch.  All layers are validated before the first
+ * launch; on a validation error nothing is enqueued. */
 int axo_layer_step(const axo_layer_t *layers, int n_layers, void *ws, size_t ws_bytes,
                    void *hip_stream);
 

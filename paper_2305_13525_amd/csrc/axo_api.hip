@@ -558,7 +558,26 @@ int axo_layer_step(const axo_layer_t* layers, int n_layers, void* ws, size_t ws_
     std::vector<Plan> plans;
     int rc = plan_chain(layers, n_layers, ws, ws_bytes, &plans);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    for (size_t i = 0; i < plans.size() && rc == AXO_OK; ++i) rc = launch(plans[i].g, plans[i].la, plans[i].lb, st);
+    const size_t n = (size_t)(n_layers > 0 ? n_layers : 0);
+    // forwards one by one, in order: a caller may feed layer i's Y to layer i+1 as X
+    for (size_t i = 0; i < n && i < plans.size() && rc == AXO_OK; ++i) rc = launch(plans[i].g, plans[i].la, plans[i].lb, st);
+    // backward, layer by layer: dgrad and wgrad of one layer never depend on each other (dgrad
+    // reads dY and W and writes dX, wgrad reads X and dY and writes dW), so the pair shares one
+    // launch when the tiled kernel takes both; pairs stay in order (dX of layer i may be the
+    // caller's dY of layer i-1)
+    for (size_t b = n; b + 1 < plans.size() && rc == AXO_OK; b += 2) {
+        const Plan& dg = plans[b];
+        const Plan& wg = plans[b + 1];
+        const bool both = dg.g.Mo > 0 && dg.g.No > 0 && wg.g.Mo > 0 && wg.g.No > 0 && !force_generic() &&
+                          tileable(dg.g, dg.la, dg.lb) && tileable(wg.g, wg.la, wg.lb);
+        if (both) {
+            const Plan* pair[2] = {&dg, &wg};
+            rc = launch_group(pair, 2, st);
+        } else {
+            rc = launch(dg.g, dg.la, dg.lb, st);
+            if (rc == AXO_OK) rc = launch(wg.g, wg.la, wg.lb, st);
+        }
+    }
     return rc;
 }
 
