@@ -538,8 +538,15 @@ int axo_bias_grad(const axo_problem_t* p, const void* dY, int64_t lddy, float* d
     g.M = (int)s.M;
     g.Nl = (int)s.Nl;
     g.accumulate = accumulate;
-    const unsigned blocks = (unsigned)((s.Nl + axo::BG_COLS - 1) / axo::BG_COLS);
-    hipLaunchKernelGGL(axo::bias_grad_kernel, dim3(blocks), dim3(axo::BG_THREADS), 0, static_cast<hipStream_t>(hip_stream), g);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    auto blocks = [&](int cols) { return (unsigned)((s.Nl + cols - 1) / cols); };
+    // the widest column block that still gives every CU a workgroup
+    if (blocks(64) >= (unsigned)NUM_CU / 4)
+        hipLaunchKernelGGL(axo::bias_grad_kernel<64>, dim3(blocks(64)), dim3(axo::BG_THREADS), 0, st, g);
+    else if (blocks(32) >= (unsigned)NUM_CU / 8)
+        hipLaunchKernelGGL(axo::bias_grad_kernel<32>, dim3(blocks(32)), dim3(axo::BG_THREADS), 0, st, g);
+    else
+        hipLaunchKernelGGL(axo::bias_grad_kernel<16>, dim3(blocks(16)), dim3(axo::BG_THREADS), 0, st, g);
     return hipGetLastError() == hipSuccess ? AXO_OK : AXO_ERR_HIP;
 }
 

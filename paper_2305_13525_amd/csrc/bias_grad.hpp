@@ -1,20 +1,20 @@
 // Bias gradient: db[n] (+)= sum_t dY[t, n], dY bf16 row-major [M x Nl], db fp32.  Memory bound:
 // it reads dY once (2 M Nl bytes) and writes Nl floats.
 //
-// One 1024-thread workgroup owns 32 columns: 4 lanes across (8 columns = one 16-byte load each)
-// by 256 lanes down the rows.  Every thread sums its rows t = r, r + 256, ... in fp32 (four loads
-// in flight per thread), the 256 partial sums of a column are added in a fixed tree through LDS,
-// and lane (0, c) writes the result: no atomics, so the result does not depend on scheduling.
-// 32 columns per workgroup (64-byte row segments) rather than 64, and 1024 threads rather than
-// 256, keep enough loads in flight to pull bandwidth from all XCDs at layer widths of a few
-// thousand columns, where the grid is smaller than the chip (measured on a 4096 x 6144 shard:
-// 1.3 TB/s with 256 threads per workgroup).
+// One 1024-thread workgroup owns COLS columns (16, 32 or 64): COLS / 8 lanes across (8 columns =
+// one 16-byte load each) by 1024 / (COLS / 8) lanes down the rows.  Every thread sums its rows
+// t = r, r + ROWS, ... in fp32 (four loads in flight per thread), the partial sums of a column are
+// added in a fixed tree through LDS, and lane (0, c) writes the result: no atomics, so the result
+// does not depend on scheduling.  The host picks the widest COLS that still gives at least 256
+// workgroups (one per CU): wide blocks read whole 128-byte lines, narrow ones keep the whole chip
+// busy at layer widths of a few thousand columns (measured on a 4096 x 6144 shard: 1.3 TB/s with
+// 256 threads and 32 columns per workgroup, 2.3 TB/s with 1024 threads).
 #pragma once
 #include "axo_common.hpp"
 
 namespace axo {
 
-constexpr int BG_COLS = 32, BG_THREADS = 1024, BG_ROWS = BG_THREADS / 4;
+constexpr int BG_THREADS = 1024;
 
 struct BiasGradArgs {
     const bf16_t* dY; int64_t lddy;
@@ -23,15 +23,17 @@ struct BiasGradArgs {
     int accumulate;  // 0: db = sums, 1: db += sums
 };
 
+template <int COLS>
 __global__ void __launch_bounds__(BG_THREADS) bias_grad_kernel(BiasGradArgs g) {
-    __shared__ float part[BG_ROWS][BG_COLS + 1];
-    const int cx = threadIdx.x & 3, ry = threadIdx.x >> 2;
-    const int col = blockIdx.x * BG_COLS + cx * 8;
+    constexpr int CX = COLS / 8, ROWS = BG_THREADS / CX;
+    __shared__ float part[ROWS][COLS + 1];
+    const int cx = threadIdx.x % CX, ry = threadIdx.x / CX;
+    const int col = blockIdx.x * COLS + cx * 8;
     const int valid = g.Nl - col;  // columns of this thread's chunk inside the matrix (may be <= 0 or >= 8)
     float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (valid >= 8) {
 #pragma unroll 4
-        for (int t = ry; t < g.M; t += BG_ROWS) {
+        for (int t = ry; t < g.M; t += ROWS) {
             const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(g.dY + (int64_t)t * g.lddy + col));
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -40,13 +42,13 @@ __global__ void __launch_bounds__(BG_THREADS) bias_grad_kernel(BiasGradArgs g) {
             }
         }
     } else if (valid > 0) {  // ragged last chunk
-        for (int t = ry; t < g.M; t += BG_ROWS)
+        for (int t = ry; t < g.M; t += ROWS)
             for (int i = 0; i < valid; ++i) s[i] += bf16_bits_to_f32(g.dY[(int64_t)t * g.lddy + col + i]);
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) part[ry][cx * 8 + i] = s[i];
     __syncthreads();
-    for (int half = BG_ROWS / 2; half >= 1; half >>= 1) {  // fixed-shape tree over the row lanes
+    for (int half = ROWS / 2; half >= 1; half >>= 1) {  // fixed-shape tree over the row lanes
         if (ry < half) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) part[ry][cx * 8 + i] += part[ry + half][cx * 8 + i];
