@@ -22,8 +22,11 @@
 // The 16x16x32 MFMA is used rather than the 32x32x16 one: at the chip's power limit a loop of
 // nothing but MFMAs on random operands sustains 2.0 PFLOP/s with the former and 1.75 with the
 // latter (two waves per SIMD).  The accumulators hold the transposed 16x16 tile (B fragment
-// first), which gives each lane 4 consecutive output columns; the epilogue rounds to bf16 once, stages the wave's sub-tile through
-// LDS and writes full 128-byte row segments.
+// first), which gives each lane 4 consecutive output columns; the epilogue rounds to bf16 once,
+// stages the wave's sub-tile through LDS and writes full 128-byte row segments.
+//
+// Two kernels share the tile body: gemm_mixed_kernel (one product per launch) and
+// gemm_group_kernel (the tiles of up to twelve independent products in one grid).
 #pragma once
 #include <type_traits>
 
