@@ -27,7 +27,7 @@
  * round-to-nearest-even, to bf16 at the store.  Leading dimensions are in elements and allow a
  * shard to be addressed in place inside a larger matrix.
  *
- * Ownership: the caller owns all buffers; the library allocates nothing, keeps no pointer after
+ * Ownership: the caller owns all buffers; the library allocates no device memory, keeps no pointer after
  * a call returns, and only enqueues work on the caller's HIP stream (no device synchronisation,
  * no host read-back).  Buffers must stay valid until the stream has executed the call.
  * Outputs must not alias inputs.  A matrix with no elements (a zero shard dimension) is never
@@ -35,7 +35,9 @@
  *
  * Errors: every function returns an int status, 0 on success, negative on error; nothing throws
  * or aborts.  All argument checks happen on the host before the first HIP call, so every status
- * except AXO_ERR_HIP can be produced without a GPU.
+ * except AXO_ERR_HIP can be produced without a GPU.  Host-side plan lists and per-shape plan caches
+ * are the library's only allocations; when one fails the call returns AXO_ERR_NO_MEMORY and has
+ * enqueued nothing or a prefix of its launches.
  */
 #ifndef AXO_H
 #define AXO_H
@@ -62,7 +64,8 @@ typedef enum axo_status {
     AXO_ERR_BAD_EPILOGUE = -8, /* unknown epilogue, or an epilogue with bias == NULL             */
     AXO_ERR_HIP = -9,          /* a HIP launch failed (the only status that needs a device)      */
     AXO_ERR_BAD_SIZE = -10,    /* T, K or N < 0, or a shard dimension beyond 2^31-1              */
-    AXO_ERR_BAD_ARG = -11      /* anything else malformed (unknown op, n_layers < 0, ...)        */
+    AXO_ERR_BAD_ARG = -11,     /* anything else malformed (unknown op, n_layers < 0, ...)        */
+    AXO_ERR_NO_MEMORY = -12    /* a host allocation of the library failed (plan lists, caches)   */
 } axo_status_t;
 
 /* The problem statement of Section 3.2: grid, this GPU's coordinate, global sizes. */
@@ -199,9 +202,19 @@ int axo_layer_step(const axo_layer_t *layers, int n_layers, void *ws, size_t ws_
  * first, so that products too small to fill the GPU on their own (a 1536 x 1536 shard is 36 tiles
  * for 256 compute units) run side by side and the chain pays one ramp-up and one tail instead of
  * one per product.  Products whose shapes the tiled kernel does not take are launched on their
- * own.  Validation, workspace, stream and error behaviour are those of axo_layer_step. */
+ * own.  The condition is checked on the host, on the byte ranges the matrices span (first to last
+ * element, so two column blocks interleaved in one buffer count as overlapping): a chain that
+ * does not meet it, or in which two outputs overlap, is enqueued exactly as axo_layer_step would.
+ * Validation, workspace, stream and error behaviour are those of axo_layer_step. */
 int axo_layer_step_grouped(const axo_layer_t *layers, int n_layers, void *ws, size_t ws_bytes,
                            void *hip_stream);
+
+/* Host only.  The condition of axo_layer_step_grouped, as that call evaluates it: *independent
+ * is set to 1 when no output range of the chain overlaps an input range or another output range
+ * (the grouped launches are taken), to 0 otherwise (the call keeps axo_layer_step's order).
+ * Pointers are compared, never dereferenced.  Errors: those of axo_layer_step's validation
+ * (with ws = NULL, ws_bytes = 0), NULL_PTR (independent). */
+int axo_layer_chain_independent(const axo_layer_t *layers, int n_layers, int *independent);
 
 #ifdef __cplusplus
 }

@@ -94,6 +94,8 @@ def library() -> ctypes.CDLL:
     L.axo_bias_grad.restype = i32
     L.axo_layer_step_grouped.argtypes = [ctypes.POINTER(Layer), i32, vp, sz, vp]
     L.axo_layer_step_grouped.restype = i32
+    L.axo_layer_chain_independent.argtypes = [ctypes.POINTER(Layer), i32, ctypes.POINTER(ctypes.c_int)]
+    L.axo_layer_chain_independent.restype = i32
     _lib = L
     return L
 
@@ -167,6 +169,13 @@ def axo_layer_step_grouped(layers: Sequence[Layer], ws: Optional[int] = None, ws
                            stream: Optional[int] = None, check: bool = True) -> int:
     rc = library().axo_layer_step_grouped(_layer_array(layers), len(layers), ws, ws_bytes, stream)
     return _check(rc, "axo_layer_step_grouped", check)
+
+
+def axo_layer_chain_independent(layers: Sequence[Layer], check: bool = True) -> Tuple[int, bool]:
+    """(status, whether axo_layer_step_grouped takes the grouped launches for this chain)."""
+    flag = ctypes.c_int(0)
+    rc = library().axo_layer_chain_independent(_layer_array(layers), len(layers), ctypes.byref(flag))
+    return _check(rc, "axo_layer_chain_independent", check), bool(flag.value)
 
 
 def axo_fc_dgrad_act(p: Problem, dY: int, lddy: int, W: int, ldw: int, pre: int, ldpre: int, act: int, dX: int,

@@ -147,18 +147,26 @@ axo::TileSched plan_tiles(int Mo, int No) {
     return sc;
 }
 
-// Launch of one tuned-kernel instantiation.  The dynamic LDS size is above the default limit, so
-// the attribute is raised once per instantiation (per process; one device per process).
+// The tuned kernels' dynamic LDS size is above the default limit, so the limit is raised once per
+// kernel and device (`raised` holds one bit per device ordinal; a process rarely sees more than
+// 8, and beyond 64 the attribute is simply set on every launch).
+bool raise_lds_limit(const void* kernel, std::atomic<uint64_t>* raised) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t)1 << dev : 0;
+    if (bit && (raised->load(std::memory_order_acquire) & bit)) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, axo::MIX_LDS_BYTES) != hipSuccess)
+        return false;
+    raised->fetch_or(bit, std::memory_order_release);
+    return true;
+}
+
+// Launch of one tuned-kernel instantiation.
 template <int LA, int LB>
 int launch_tile(const GemmArgs& g, hipStream_t st) {
     auto kern = axo::gemm_mixed_kernel<LA, LB>;
-    static std::atomic<int> ready{0};
-    if (!ready.load(std::memory_order_acquire)) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                axo::MIX_LDS_BYTES) != hipSuccess)
-            return AXO_ERR_HIP;
-        ready.store(1, std::memory_order_release);
-    }
+    static std::atomic<uint64_t> raised{0};
+    if (!raise_lds_limit(reinterpret_cast<const void*>(kern), &raised)) return AXO_ERR_HIP;
     const axo::TileSched sc = plan_tiles(g.Mo, g.No);
     const int blocks = sc.n_big + sc.tiles_m * sc.small_cols;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(axo::TILE_THREADS), axo::MIX_LDS_BYTES, st, g, sc);
@@ -281,13 +289,8 @@ struct Plan {
 };
 
 int launch_group(const Plan* const* plans, int n, hipStream_t st) {
-    static std::atomic<int> ready{0};
-    if (!ready.load(std::memory_order_acquire)) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(axo::gemm_group_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, axo::MIX_LDS_BYTES) != hipSuccess)
-            return AXO_ERR_HIP;
-        ready.store(1, std::memory_order_release);
-    }
+    static std::atomic<uint64_t> raised{0};
+    if (!raise_lds_limit(reinterpret_cast<const void*>(axo::gemm_group_kernel), &raised)) return AXO_ERR_HIP;
     std::vector<GroupItem> items(n);
     for (int i = 0; i < n; ++i)
         items[i] = {plans[i]->g.Mo, plans[i]->g.No, plans[i]->g.R, layout_pair(plans[i]->la, plans[i]->lb)};
@@ -437,6 +440,86 @@ int plan_wgrad_acc(const axo_problem_t* p, const void* X, int64_t ldx, const voi
     return AXO_OK;
 }
 
+// ---- dependence check for the grouped step ---------------------------------------------------
+// Byte range [lo, hi) that a matrix argument covers (rows x row_len elements of elem bytes, rows
+// ld elements apart); empty matrices cover nothing.
+struct Range {
+    uintptr_t lo, hi;
+};
+bool matrix_range(const void* ptr, int64_t ld, int64_t rows, int64_t row_len, int elem, Range* r) {
+    if (!ptr || rows <= 0 || row_len <= 0) return false;
+    r->lo = reinterpret_cast<uintptr_t>(ptr);
+    r->hi = r->lo + (uintptr_t)(((rows - 1) * ld + row_len) * elem);
+    return true;
+}
+void operand_ranges(const Plan& pl, std::vector<Range>* in, std::vector<Range>* out) {
+    const GemmArgs& g = pl.g;
+    Range r;
+    // A(i, r): KC is Mo rows of R elements, MC is R rows of Mo elements; B likewise with No
+    if (pl.la == axo::KC ? matrix_range(g.A, g.lda, g.Mo, g.R, 2, &r) : matrix_range(g.A, g.lda, g.R, g.Mo, 2, &r))
+        in->push_back(r);
+    if (pl.lb == axo::KC ? matrix_range(g.B, g.ldb, g.No, g.R, 2, &r) : matrix_range(g.B, g.ldb, g.R, g.No, 2, &r))
+        in->push_back(r);
+    if (g.add_bias && matrix_range(g.bias, g.No, 1, g.No, 2, &r)) in->push_back(r);
+    if (matrix_range(g.aux, g.ldaux, g.Mo, g.No, 2, &r)) in->push_back(r);
+    if (matrix_range(g.C, g.ldc, g.Mo, g.No, g.epilogue == axo::EPI_ACC_F32 ? 4 : 2, &r)) out->push_back(r);
+}
+// True when no output of the chain overlaps an input of the chain or another output: the
+// products may then run in any order.  (Ranges, not elements: two interleaved column blocks of one
+// buffer count as overlapping, which only costs the grouping.)
+bool products_independent(const std::vector<Plan>& plans) {
+    std::vector<Range> in, out;
+    for (const Plan& pl : plans) operand_ranges(pl, &in, &out);
+    auto by_lo = [](const Range& a, const Range& b) { return a.lo < b.lo; };
+    std::sort(out.begin(), out.end(), by_lo);
+    for (size_t i = 1; i < out.size(); ++i)
+        if (out[i].lo < out[i - 1].hi) return false;  // sorted and pairwise disjoint from here on
+    for (const Range& r : in) {
+        // first output that ends after r begins
+        auto it = std::upper_bound(out.begin(), out.end(), r.lo, [](uintptr_t v, const Range& o) { return v < o.hi; });
+        if (it != out.end() && it->lo < r.hi) return false;
+    }
+    return true;
+}
+
+// the chain in dependence order: see axo_layer_step
+int enqueue_in_order(const std::vector<Plan>& plans, size_t n, hipStream_t st) {
+    int rc = AXO_OK;
+    // forwards one by one, in order: a caller may feed layer i's Y to layer i+1 as X
+    for (size_t i = 0; i < n && i < plans.size() && rc == AXO_OK; ++i) rc = launch(plans[i].g, plans[i].la, plans[i].lb, st);
+    // backward, layer by layer: dgrad and wgrad of one layer never depend on each other (dgrad
+    // reads dY and W and writes dX, wgrad reads X and dY and writes dW), so the pair shares one
+    // launch when the tiled kernel takes both; pairs stay in order (dX of layer i may be the
+    // caller's dY of layer i-1)
+    for (size_t b = n; b + 1 < plans.size() && rc == AXO_OK; b += 2) {
+        const Plan& dg = plans[b];
+        const Plan& wg = plans[b + 1];
+        const bool both = dg.g.Mo > 0 && dg.g.No > 0 && wg.g.Mo > 0 && wg.g.No > 0 && !force_generic() &&
+                          tileable(dg.g, dg.la, dg.lb) && tileable(wg.g, wg.la, wg.lb);
+        if (both) {
+            const Plan* pair[2] = {&dg, &wg};
+            rc = launch_group(pair, 2, st);
+        } else {
+            rc = launch(dg.g, dg.la, dg.lb, st);
+            if (rc == AXO_OK) rc = launch(wg.g, wg.la, wg.lb, st);
+        }
+    }
+    return rc;
+}
+
+// No exception leaves the library: the planners keep their lists and caches in standard
+// containers, whose allocations can fail.
+template <typename F>
+int guarded(F&& body) noexcept {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        return AXO_ERR_NO_MEMORY;
+    } catch (...) {
+        return AXO_ERR_BAD_ARG;
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -457,6 +540,7 @@ const char* axo_status_string(int status) {
         case AXO_ERR_HIP: return "HIP launch failed";
         case AXO_ERR_BAD_SIZE: return "negative size or shard dimension beyond 2^31-1";
         case AXO_ERR_BAD_ARG: return "malformed argument";
+        case AXO_ERR_NO_MEMORY: return "host allocation failed";
         default: return "unknown status";
     }
 }
@@ -484,42 +568,52 @@ size_t axo_workspace_bytes(const axo_problem_t* p, int op) {
 
 int axo_fc_fwd(const axo_problem_t* p, const void* X, int64_t ldx, const void* W, int64_t ldw, const void* bias,
                int epilogue, void* Y, int64_t ldy, void* ws, size_t ws_bytes, void* hip_stream) {
-    Plan pl;
-    int rc = plan_fwd(p, X, ldx, W, ldw, bias, epilogue, Y, ldy, ws, ws_bytes, &pl);
-    if (rc) return rc;
-    return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+    return guarded([&]() -> int {
+        Plan pl;
+        int rc = plan_fwd(p, X, ldx, W, ldw, bias, epilogue, Y, ldy, ws, ws_bytes, &pl);
+        if (rc) return rc;
+        return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+    });
 }
 
 int axo_fc_dgrad(const axo_problem_t* p, const void* dY, int64_t lddy, const void* W, int64_t ldw, void* dX,
                  int64_t lddx, void* ws, size_t ws_bytes, void* hip_stream) {
-    Plan pl;
-    int rc = plan_dgrad(p, dY, lddy, W, ldw, dX, lddx, ws, ws_bytes, &pl);
-    if (rc) return rc;
-    return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+    return guarded([&]() -> int {
+        Plan pl;
+        int rc = plan_dgrad(p, dY, lddy, W, ldw, dX, lddx, ws, ws_bytes, &pl);
+        if (rc) return rc;
+        return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+    });
 }
 
 int axo_fc_wgrad(const axo_problem_t* p, const void* X, int64_t ldx, const void* dY, int64_t lddy, void* dW,
                  int64_t lddw, void* ws, size_t ws_bytes, void* hip_stream) {
-    Plan pl;
-    int rc = plan_wgrad(p, X, ldx, dY, lddy, dW, lddw, ws, ws_bytes, &pl);
-    if (rc) return rc;
-    return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+    return guarded([&]() -> int {
+        Plan pl;
+        int rc = plan_wgrad(p, X, ldx, dY, lddy, dW, lddw, ws, ws_bytes, &pl);
+        if (rc) return rc;
+        return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+    });
 }
 
 int axo_fc_dgrad_act(const axo_problem_t* p, const void* dY, int64_t lddy, const void* W, int64_t ldw, const void* pre,
                      int64_t ldpre, int act, void* dX, int64_t lddx, void* ws, size_t ws_bytes, void* hip_stream) {
-    Plan pl;
-    int rc = plan_dgrad_act(p, dY, lddy, W, ldw, pre, ldpre, act, dX, lddx, ws, ws_bytes, &pl);
-    if (rc) return rc;
-    return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+    return guarded([&]() -> int {
+        Plan pl;
+        int rc = plan_dgrad_act(p, dY, lddy, W, ldw, pre, ldpre, act, dX, lddx, ws, ws_bytes, &pl);
+        if (rc) return rc;
+        return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+    });
 }
 
 int axo_fc_wgrad_acc(const axo_problem_t* p, const void* X, int64_t ldx, const void* dY, int64_t lddy, float* dW,
                      int64_t lddw, void* ws, size_t ws_bytes, void* hip_stream) {
-    Plan pl;
-    int rc = plan_wgrad_acc(p, X, ldx, dY, lddy, dW, lddw, ws, ws_bytes, &pl);
-    if (rc) return rc;
-    return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+    return guarded([&]() -> int {
+        Plan pl;
+        int rc = plan_wgrad_acc(p, X, ldx, dY, lddy, dW, lddw, ws, ws_bytes, &pl);
+        if (rc) return rc;
+        return launch(pl.g, pl.la, pl.lb, static_cast<hipStream_t>(hip_stream));
+    });
 }
 
 int axo_bias_grad(const axo_problem_t* p, const void* dY, int64_t lddy, float* db, int accumulate, void* hip_stream) {
@@ -562,55 +656,53 @@ size_t axo_layer_step_workspace_bytes(const axo_layer_t* layers, int n_layers) {
 }
 
 int axo_layer_step(const axo_layer_t* layers, int n_layers, void* ws, size_t ws_bytes, void* hip_stream) {
-    std::vector<Plan> plans;
-    int rc = plan_chain(layers, n_layers, ws, ws_bytes, &plans);
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const size_t n = (size_t)(n_layers > 0 ? n_layers : 0);
-    // forwards one by one, in order: a caller may feed layer i's Y to layer i+1 as X
-    for (size_t i = 0; i < n && i < plans.size() && rc == AXO_OK; ++i) rc = launch(plans[i].g, plans[i].la, plans[i].lb, st);
-    // backward, layer by layer: dgrad and wgrad of one layer never depend on each other (dgrad
-    // reads dY and W and writes dX, wgrad reads X and dY and writes dW), so the pair shares one
-    // launch when the tiled kernel takes both; pairs stay in order (dX of layer i may be the
-    // caller's dY of layer i-1)
-    for (size_t b = n; b + 1 < plans.size() && rc == AXO_OK; b += 2) {
-        const Plan& dg = plans[b];
-        const Plan& wg = plans[b + 1];
-        const bool both = dg.g.Mo > 0 && dg.g.No > 0 && wg.g.Mo > 0 && wg.g.No > 0 && !force_generic() &&
-                          tileable(dg.g, dg.la, dg.lb) && tileable(wg.g, wg.la, wg.lb);
-        if (both) {
-            const Plan* pair[2] = {&dg, &wg};
-            rc = launch_group(pair, 2, st);
-        } else {
-            rc = launch(dg.g, dg.la, dg.lb, st);
-            if (rc == AXO_OK) rc = launch(wg.g, wg.la, wg.lb, st);
-        }
-    }
-    return rc;
+    return guarded([&]() -> int {
+        std::vector<Plan> plans;
+        const int rc = plan_chain(layers, n_layers, ws, ws_bytes, &plans);
+        if (rc != AXO_OK) return rc;
+        return enqueue_in_order(plans, (size_t)(n_layers > 0 ? n_layers : 0), static_cast<hipStream_t>(hip_stream));
+    });
+}
+
+int axo_layer_chain_independent(const axo_layer_t* layers, int n_layers, int* independent) {
+    return guarded([&]() -> int {
+        if (!independent) return AXO_ERR_NULL_PTR;
+        std::vector<Plan> plans;
+        const int rc = plan_chain(layers, n_layers, nullptr, 0, &plans);
+        if (rc != AXO_OK) return rc;
+        *independent = products_independent(plans) ? 1 : 0;
+        return AXO_OK;
+    });
 }
 
 int axo_layer_step_grouped(const axo_layer_t* layers, int n_layers, void* ws, size_t ws_bytes, void* hip_stream) {
-    std::vector<Plan> plans;
-    int rc = plan_chain(layers, n_layers, ws, ws_bytes, &plans);
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    std::vector<const Plan*> group;
-    auto flush = [&]() {
-        if (group.empty() || rc != AXO_OK) return;
-        rc = group.size() == 1 ? launch_tile_layout(group[0]->g, group[0]->la, group[0]->lb, st)
-                               : launch_group(group.data(), (int)group.size(), st);
-        group.clear();
-    };
-    for (size_t i = 0; i < plans.size() && rc == AXO_OK; ++i) {
-        const Plan& pl = plans[i];
-        if (pl.g.Mo == 0 || pl.g.No == 0) continue;
-        if (!tileable(pl.g, pl.la, pl.lb) || force_generic()) {
-            rc = launch_generic(pl.g, pl.la, pl.lb, st);
-            continue;
+    return guarded([&]() -> int {
+        std::vector<Plan> plans;
+        int rc = plan_chain(layers, n_layers, ws, ws_bytes, &plans);
+        if (rc != AXO_OK) return rc;
+        hipStream_t st = static_cast<hipStream_t>(hip_stream);
+        // a chain with a dependence between its products keeps the order of axo_layer_step
+        if (!products_independent(plans)) return enqueue_in_order(plans, (size_t)n_layers, st);
+        std::vector<const Plan*> group;
+        auto flush = [&]() {
+            if (group.empty() || rc != AXO_OK) return;
+            rc = group.size() == 1 ? launch_tile_layout(group[0]->g, group[0]->la, group[0]->lb, st)
+                                   : launch_group(group.data(), (int)group.size(), st);
+            group.clear();
+        };
+        for (size_t i = 0; i < plans.size() && rc == AXO_OK; ++i) {
+            const Plan& pl = plans[i];
+            if (pl.g.Mo == 0 || pl.g.No == 0) continue;
+            if (!tileable(pl.g, pl.la, pl.lb) || force_generic()) {
+                rc = launch_generic(pl.g, pl.la, pl.lb, st);
+                continue;
+            }
+            group.push_back(&pl);
+            if ((int)group.size() == axo::GROUP_MAX_PRODUCTS) flush();
         }
-        group.push_back(&pl);
-        if ((int)group.size() == axo::GROUP_MAX_PRODUCTS) flush();
-    }
-    flush();
-    return rc;
+        flush();
+        return rc;
+    });
 }
 
 }  // extern "C"

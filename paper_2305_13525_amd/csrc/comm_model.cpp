@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <new>
 #include <vector>
 
 #include "../../include/axo.h"
@@ -161,56 +162,63 @@ int axo_comm_rank_configs(int32_t n_gpus, const axo_comm_net_t* net, const axo_c
     if (!(bytes_per_element > 0.0)) return AXO_ERR_BAD_SIZE;
     for (int i = 0; i < n_layers; ++i)
         if ((rc = check_layer(&layers[i]))) return rc;
-    struct Entry {
-        axo_comm_config_t c;
-        double t;
-    };
-    std::vector<Entry> found;
-    for (int32_t gx = 1; gx <= n_gpus; ++gx) {
-        if (n_gpus % gx) continue;
-        for (int32_t gy = 1; gy <= n_gpus / gx; ++gy) {
-            if ((n_gpus / gx) % gy) continue;
-            const int32_t rest = n_gpus / gx / gy;
-            for (int32_t gz = 1; gz <= rest; ++gz) {
-                if (rest % gz) continue;
-                const axo_comm_config_t c = {gx, gy, gz, rest / gz};
-                if (batch_rows % c.Gdata != 0 || (batch_rows / c.Gdata) % c.Gz != 0) continue;
-                bool ok = true;
-                for (int i = 0; i < n_layers && ok; ++i) {
-                    const int32_t gk = layers[i].transposed ? gy : gx, gn = layers[i].transposed ? gx : gy;
-                    ok = layers[i].k % gk == 0 && layers[i].n % gn == 0;
+    // the candidate list lives in a standard container: no exception may leave the library
+    try {
+        struct Entry {
+            axo_comm_config_t c;
+            double t;
+        };
+        std::vector<Entry> found;
+        for (int32_t gx = 1; gx <= n_gpus; ++gx) {
+            if (n_gpus % gx) continue;
+            for (int32_t gy = 1; gy <= n_gpus / gx; ++gy) {
+                if ((n_gpus / gx) % gy) continue;
+                const int32_t rest = n_gpus / gx / gy;
+                for (int32_t gz = 1; gz <= rest; ++gz) {
+                    if (rest % gz) continue;
+                    const axo_comm_config_t c = {gx, gy, gz, rest / gz};
+                    if (batch_rows % c.Gdata != 0 || (batch_rows / c.Gdata) % c.Gz != 0) continue;
+                    bool ok = true;
+                    for (int i = 0; i < n_layers && ok; ++i) {
+                        const int32_t gk = layers[i].transposed ? gy : gx, gn = layers[i].transposed ? gx : gy;
+                        ok = layers[i].k % gk == 0 && layers[i].n % gn == 0;
+                    }
+                    if (!ok) continue;
+                    double t = 0.0;
+                    rc = axo_comm_model_time(&c, net, layers, n_layers, batch_rows, bytes_per_element, &t, nullptr);
+                    if (rc) return rc;
+                    found.push_back({c, t});
                 }
-                if (!ok) continue;
-                double t = 0.0;
-                rc = axo_comm_model_time(&c, net, layers, n_layers, batch_rows, bytes_per_element, &t, nullptr);
-                if (rc) return rc;
-                found.push_back({c, t});
             }
         }
+        std::stable_sort(found.begin(), found.end(), [](const Entry& a, const Entry& b) { return a.t < b.t; });
+        // Configurations whose modelled times are equal as real numbers can differ in the last bits
+        // of their floating-point sums: runs of times within 1e-12 (relative) of their neighbour are
+        // ties, ordered by (Gx, Gy, Gz, Gdata) ascending.
+        auto lex = [](const Entry& a, const Entry& b) {
+            if (a.c.Gx != b.c.Gx) return a.c.Gx < b.c.Gx;
+            if (a.c.Gy != b.c.Gy) return a.c.Gy < b.c.Gy;
+            if (a.c.Gz != b.c.Gz) return a.c.Gz < b.c.Gz;
+            return a.c.Gdata < b.c.Gdata;
+        };
+        for (size_t i = 0; i < found.size();) {
+            size_t j = i + 1;
+            while (j < found.size() && found[j].t - found[j - 1].t <= 1e-12 * found[j].t) ++j;
+            std::sort(found.begin() + i, found.begin() + j, lex);
+            i = j;
+        }
+        *n_found = (int32_t)found.size();
+        const int32_t n_out = std::min<int32_t>(*n_found, max_out < 0 ? 0 : max_out);
+        for (int32_t i = 0; i < n_out; ++i) {
+            if (configs) configs[i] = found[i].c;
+            if (times) times[i] = found[i].t;
+        }
+        return AXO_OK;
+    } catch (const std::bad_alloc&) {
+        return AXO_ERR_NO_MEMORY;
+    } catch (...) {
+        return AXO_ERR_BAD_ARG;
     }
-    std::stable_sort(found.begin(), found.end(), [](const Entry& a, const Entry& b) { return a.t < b.t; });
-    // Configurations whose modelled times are equal as real numbers can differ in the last bits
-    // of their floating-point sums: runs of times within 1e-12 (relative) of their neighbour are
-    // ties, ordered by (Gx, Gy, Gz, Gdata) ascending.
-    auto lex = [](const Entry& a, const Entry& b) {
-        if (a.c.Gx != b.c.Gx) return a.c.Gx < b.c.Gx;
-        if (a.c.Gy != b.c.Gy) return a.c.Gy < b.c.Gy;
-        if (a.c.Gz != b.c.Gz) return a.c.Gz < b.c.Gz;
-        return a.c.Gdata < b.c.Gdata;
-    };
-    for (size_t i = 0; i < found.size();) {
-        size_t j = i + 1;
-        while (j < found.size() && found[j].t - found[j - 1].t <= 1e-12 * found[j].t) ++j;
-        std::sort(found.begin() + i, found.begin() + j, lex);
-        i = j;
-    }
-    *n_found = (int32_t)found.size();
-    const int32_t n_out = std::min<int32_t>(*n_found, max_out < 0 ? 0 : max_out);
-    for (int32_t i = 0; i < n_out; ++i) {
-        if (configs) configs[i] = found[i].c;
-        if (times) times[i] = found[i].t;
-    }
-    return AXO_OK;
 }
 
 int axo_comm_rank_to_coord(const axo_comm_config_t* cfg, int64_t rank, int32_t coord[4]) {

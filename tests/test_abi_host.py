@@ -14,8 +14,8 @@ import paper_2305_13525_amd as axo
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "axo.h")
 
-OK, BAD_GRID, BAD_COORD, INDIVISIBLE, NULL_PTR, MISALIGNED, BAD_LD, WORKSPACE, BAD_EPI, HIP, BAD_SIZE, BAD_ARG = (
-    0, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10, -11)
+OK, BAD_GRID, BAD_COORD, INDIVISIBLE, NULL_PTR, MISALIGNED, BAD_LD, WORKSPACE, BAD_EPI, HIP, BAD_SIZE, BAD_ARG, NO_MEMORY = (
+    0, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10, -11, -12)
 
 
 def declared_functions():
@@ -30,7 +30,8 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"axo_fc_fwd", "axo_fc_dgrad", "axo_fc_wgrad", "axo_layer_step", "axo_shard_dims",
             "axo_workspace_bytes", "axo_status_string", "axo_version",
-            "axo_layer_step_workspace_bytes", "axo_layer_step_grouped", "axo_comm_rank_configs",
+            "axo_layer_step_workspace_bytes", "axo_layer_step_grouped", "axo_layer_chain_independent",
+            "axo_comm_rank_configs",
             "axo_comm_layer_time"} <= set(names)
     lib = ctypes.CDLL(axo.library_path())
     for n in names:
@@ -169,6 +170,44 @@ def test_layer_step_validates_whole_chain_first(entry):
     assert getattr(axo.library(), entry)(None, 2, None, 0, None) == NULL_PTR
     assert getattr(axo.library(), entry)(None, -1, None, 0, None) == BAD_ARG
     assert axo.axo_layer_step_workspace_bytes([good, bad]) >= 0
+
+
+def test_chain_independence_is_decided_on_byte_ranges():
+    """axo_layer_chain_independent (host only; the addresses are made up and never dereferenced):
+    what axo_layer_step_grouped checks before it lets the products of a chain share launches."""
+    M, K, N = 64, 32, 48
+    p = axo.Problem.make((1, 1, 1), (0, 0, 0), M, K, N)
+    base = 1 << 20
+
+    def layer(X, W, Y, dY, dX, dW, ldx=K, ldy=N):
+        return axo.Layer(p, 0, 0, X, ldx, W, N, None, Y, ldy, dY, N, dX, K, dW, N)
+
+    step = 1 << 16  # far more than any of the matrices spans
+    a = [base + i * step for i in range(16)]
+    l0 = layer(a[0], a[1], a[2], a[3], a[4], a[5])
+    l1 = layer(a[6], a[7], a[8], a[9], a[10], a[11])
+    assert axo.axo_layer_chain_independent([]) == (OK, True)
+    assert axo.axo_layer_chain_independent([l0, l1]) == (OK, True)
+    # the same weight read by two layers is no dependence
+    assert axo.axo_layer_chain_independent([l0, layer(a[6], a[1], a[8], a[9], a[10], a[11])]) == (OK, True)
+    # layer one reads what layer zero writes
+    assert axo.axo_layer_chain_independent([l0, layer(a[2], a[7], a[8], a[9], a[10], a[11])]) == (OK, False)
+    # layer zero's dY is layer one's dX
+    assert axo.axo_layer_chain_independent([l0, layer(a[6], a[7], a[8], a[9], a[3], a[11])]) == (OK, False)
+    # two layers write the same dW
+    assert axo.axo_layer_chain_independent([l0, layer(a[6], a[7], a[8], a[9], a[10], a[5])]) == (OK, False)
+    # an output that begins on the last byte pair of an input: X spans (M-1)*K + K elements
+    x_bytes = ((M - 1) * K + K) * 2
+    assert axo.axo_layer_chain_independent([layer(a[0], a[1], a[0] + x_bytes - 16, a[3], a[4], a[5])]) == (OK, False)
+    assert axo.axo_layer_chain_independent([layer(a[0], a[1], a[0] + x_bytes, a[3], a[4], a[5])]) == (OK, True)
+    # column blocks interleaved in one buffer (ld twice the row length) count as overlapping
+    assert axo.axo_layer_chain_independent(
+        [layer(a[0], a[1], a[2], a[3], a[4], a[5], ldy=2 * N),
+         layer(a[6], a[7], a[2] + 2 * N, a[9], a[10], a[11], ldy=2 * N)]) == (OK, False)
+    # validation comes first
+    bad = axo.Layer(p, 0, 0, a[0], K, a[1], N, None, a[2], N, a[3], N, None, K, a[5], N)
+    assert axo.axo_layer_chain_independent([bad], check=False)[0] == NULL_PTR
+    assert axo.library().axo_layer_chain_independent(None, 0, None) == NULL_PTR
 
 
 def test_missing_library_fails_loudly(monkeypatch):

@@ -307,3 +307,33 @@ def test_grouped_step_mixed_shapes_against_oracle():
         gu.assert_close(oracle, gu.to_host(t["Y"]), oracle.fc_fwd(Xb, Wb, bias_b if epi else None, epi), tag + " fwd")
         gu.assert_close(oracle, gu.to_host(t["dX"]), oracle.fc_dgrad(dYb, Wb), tag + " dgrad")
         gu.assert_close(oracle, gu.to_host(t["dW"]), oracle.fc_wgrad(Xb, dYb), tag + " wgrad")
+
+
+@pytest.mark.parametrize("step", ["axo_layer_step", "axo_layer_step_grouped"])
+def test_step_with_dependent_layers(step):
+    """A chain whose products depend on each other: layer one reads the Y that layer zero writes,
+    and layer zero's dY is the dX that layer one writes.  axo_layer_step runs it in dependence
+    order; axo_layer_step_grouped has to notice the overlap and do the same.  The second product
+    of each dependence is checked against the oracle applied to the bits the first one produced."""
+    M, K0, N0, N1 = 512, 256, 512, 384
+    Xb, W0b, _ = rand_trio(M, K0, N0, 950)
+    _, W1b, dY1b = rand_trio(M, N0, N1, 951)
+    X, W0, W1, dY1 = gu.to_dev(Xb), gu.to_dev(W0b), gu.to_dev(W1b), gu.to_dev(dY1b)
+    Y0, Y1 = gu.empty_dev(M, N0), gu.empty_dev(M, N1)
+    dX1, dX0 = gu.empty_dev(M, N0), gu.empty_dev(M, K0)
+    dW0, dW1 = gu.empty_dev(K0, N0), gu.empty_dev(N0, N1)
+    layers = [
+        axo.Layer(P(M, K0, N0), 0, 0, X.data_ptr(), K0, W0.data_ptr(), N0, None, Y0.data_ptr(), N0,
+                  dX1.data_ptr(), N0, dX0.data_ptr(), K0, dW0.data_ptr(), N0),
+        axo.Layer(P(M, N0, N1), 0, 0, Y0.data_ptr(), N0, W1.data_ptr(), N1, None, Y1.data_ptr(), N1,
+                  dY1.data_ptr(), N1, dX1.data_ptr(), N0, dW1.data_ptr(), N1),
+    ]
+    getattr(axo, step)(layers, None, 0, gu.stream())
+    torch.cuda.synchronize()
+    Y0b, dX1b = gu.to_host(Y0), gu.to_host(dX1)
+    gu.assert_close(oracle, Y0b, oracle.fc_fwd(Xb, W0b), "fwd 0")
+    gu.assert_close(oracle, gu.to_host(Y1), oracle.fc_fwd(Y0b, W1b), "fwd 1 on fwd 0's output")
+    gu.assert_close(oracle, dX1b, oracle.fc_dgrad(dY1b, W1b), "dgrad 1")
+    gu.assert_close(oracle, gu.to_host(dW1), oracle.fc_wgrad(Y0b, dY1b), "wgrad 1 on fwd 0's output")
+    gu.assert_close(oracle, gu.to_host(dX0), oracle.fc_dgrad(dX1b, W0b), "dgrad 0 on dgrad 1's output")
+    gu.assert_close(oracle, gu.to_host(dW0), oracle.fc_wgrad(Xb, dX1b), "wgrad 0 on dgrad 1's output")
