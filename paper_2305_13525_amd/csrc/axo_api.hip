@@ -118,6 +118,10 @@ double makespan(int n_big, int n_small) {
     return end;
 }
 
+// Start-up phase shift of a single-product launch (see start_stagger): 8 phases 1920 cycles
+// apart, once the launch has a workgroup for every CU (a smaller one has no chip-wide burst).
+int stagger_units(int blocks) { return blocks >= NUM_CU ? 3 : 0; }
+
 // Choose how many 256-wide tile columns to use; the remaining columns become 128-wide tiles.
 // Plans are cached per output shape (the search simulates the dispatch).
 axo::TileSched plan_tiles(int Mo, int No) {
@@ -143,6 +147,7 @@ axo::TileSched plan_tiles(int Mo, int No) {
     sc.small_cols = (No - best_cols * 256) / 128;
     sc.n_big = sc.tiles_m * sc.big_cols;
     sc.group_m = sc.tiles_m < 4 ? sc.tiles_m : 4;
+    sc.stagger = stagger_units(sc.n_big + sc.tiles_m * sc.small_cols);
     if (cache.size() < 4096) cache[{Mo, No}] = sc;
     return sc;
 }
