@@ -26,10 +26,10 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
 # (2.000 KiB per FETCH_SIZE count, 1.000 KiB per WRITE_SIZE count).  Keyed by (workload, product);
 # "group" is the single launch of the grouped step.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg2", "fwd"): int((82047.12 * 2.0 + 49171.62) * 1024),
-    ("cfg2", "dgrad"): int((98366.64 * 2.0 + 16387.68) * 1024),
-    ("cfg2", "wgrad"): int((82011.64 * 2.0 + 24580.39) * 1024),
-    ("cfg2", "group"): int((306171.62 * 2.0 + 90119.30) * 1024),
+    ("cfg2", "fwd"): int((82100.9 * 2.0 + 49152.0) * 1024),
+    ("cfg2", "dgrad"): int((98372.0 * 2.0 + 16385.4) * 1024),
+    ("cfg2", "wgrad"): int((82012.6 * 2.0 + 24581.5) * 1024),
+    ("cfg2", "group"): int((305489.7 * 2.0 + 90116.2) * 1024),
 }
 
 
