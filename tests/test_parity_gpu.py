@@ -337,3 +337,34 @@ def test_step_with_dependent_layers(step):
     gu.assert_close(oracle, gu.to_host(dW1), oracle.fc_wgrad(Y0b, dY1b), "wgrad 1 on fwd 0's output")
     gu.assert_close(oracle, gu.to_host(dX0), oracle.fc_dgrad(dX1b, W0b), "dgrad 0 on dgrad 1's output")
     gu.assert_close(oracle, gu.to_host(dW0), oracle.fc_wgrad(Xb, dX1b), "wgrad 0 on dgrad 1's output")
+
+
+@pytest.mark.parametrize("ld_elems,what", [(4_300_000, "tiled kernel, byte offsets above 2^31"),
+                                           (8_400_000, "span above 4 GiB: general kernel")])
+def test_very_large_leading_dimensions(ld_elems, what):
+    """The largest strides the library takes.  Every input is a 256-row slice of a buffer whose rows
+    are ld_elems apart.  At 4.3 M elements the 256 rows a workgroup walks span 2.2 GB: the tiled
+    kernel still takes them, with unsigned 32-bit byte offsets above 2^31.  At 8.4 M the span
+    passes 4 GiB and the library has to route the product to the general kernel (64-bit indices)."""
+    M = Kl = Nl = 256
+    Xb, Wb, dYb = rand_trio(M, Kl, Nl, 970)
+    held = []
+
+    def wide(bits):
+        big = torch.empty((bits.shape[0], ld_elems), dtype=torch.int16, device="cuda:0")
+        held.append(big)
+        view = big[:, :bits.shape[1]]
+        view.copy_(gu.to_dev(bits))
+        return view
+
+    X, W, dY = wide(Xb), wide(Wb), wide(dYb)
+    assert gu.ld(X) == ld_elems and X.data_ptr() % 16 == 0
+    Y, dX, dW = gu.empty_dev(M, Nl), gu.empty_dev(M, Kl), gu.empty_dev(Kl, Nl)
+    p = P(M, Kl, Nl)
+    keep = [gu.run_fwd(p, X, W, Y), gu.run_dgrad(p, dY, W, dX), gu.run_wgrad(p, X, dY, dW)]
+    torch.cuda.synchronize()
+    gu.assert_close(oracle, gu.to_host(Y), oracle.fc_fwd(Xb, Wb), what + " fwd")
+    gu.assert_close(oracle, gu.to_host(dX), oracle.fc_dgrad(dYb, Wb), what + " dgrad")
+    gu.assert_close(oracle, gu.to_host(dW), oracle.fc_wgrad(Xb, dYb), what + " wgrad")
+    del keep, held, X, W, dY
+    torch.cuda.empty_cache()
