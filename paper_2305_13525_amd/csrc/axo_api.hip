@@ -266,16 +266,10 @@ std::vector<int> plan_group(const std::vector<GroupItem>& items) {
     return cols;
 }
 
-// One launch over the tiles of all given products (each tileable and non-empty, at most
-// GROUP_MAX_PRODUCTS of them).
-bool force_generic() {
-    static const bool v = [] { const char* e = getenv("AXO_FORCE_GENERIC"); return e && e[0] == '1'; }();
-    return v;
-}
-
+// One product: the tuned kernel when it takes the shape, the general kernel otherwise.
 int launch(const GemmArgs& g, int la, int lb, hipStream_t st) {
     if (g.Mo == 0 || g.No == 0) return AXO_OK;
-    if (tileable(g, la, lb) && !force_generic()) return launch_tile_layout(g, la, lb, st);
+    if (tileable(g, la, lb)) return launch_tile_layout(g, la, lb, st);
     return launch_generic(g, la, lb, st);
 }
 
@@ -293,6 +287,8 @@ struct Plan {
     int la, lb;
 };
 
+// One launch over the tiles of all given products (each tileable and non-empty, at most
+// GROUP_MAX_PRODUCTS of them).
 int launch_group(const Plan* const* plans, int n, hipStream_t st) {
     static std::atomic<uint64_t> raised{0};
     if (!raise_lds_limit(reinterpret_cast<const void*>(axo::gemm_group_kernel), &raised)) return AXO_ERR_HIP;
@@ -499,8 +495,8 @@ int enqueue_in_order(const std::vector<Plan>& plans, size_t n, hipStream_t st) {
     for (size_t b = n; b + 1 < plans.size() && rc == AXO_OK; b += 2) {
         const Plan& dg = plans[b];
         const Plan& wg = plans[b + 1];
-        const bool both = dg.g.Mo > 0 && dg.g.No > 0 && wg.g.Mo > 0 && wg.g.No > 0 && !force_generic() &&
-                          tileable(dg.g, dg.la, dg.lb) && tileable(wg.g, wg.la, wg.lb);
+        const bool both = dg.g.Mo > 0 && dg.g.No > 0 && wg.g.Mo > 0 && wg.g.No > 0 && tileable(dg.g, dg.la, dg.lb) &&
+                          tileable(wg.g, wg.la, wg.lb);
         if (both) {
             const Plan* pair[2] = {&dg, &wg};
             rc = launch_group(pair, 2, st);
@@ -698,7 +694,7 @@ int axo_layer_step_grouped(const axo_layer_t* layers, int n_layers, void* ws, si
         for (size_t i = 0; i < plans.size() && rc == AXO_OK; ++i) {
             const Plan& pl = plans[i];
             if (pl.g.Mo == 0 || pl.g.No == 0) continue;
-            if (!tileable(pl.g, pl.la, pl.lb) || force_generic()) {
+            if (!tileable(pl.g, pl.la, pl.lb)) {
                 rc = launch_generic(pl.g, pl.la, pl.lb, st);
                 continue;
             }
