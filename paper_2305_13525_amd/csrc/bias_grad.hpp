@@ -5,10 +5,12 @@
 // one 16-byte load each) by 1024 / (COLS / 8) lanes down the rows.  Every thread sums its rows
 // t = r, r + ROWS, ... in fp32 (four loads in flight per thread), the partial sums of a column are
 // added in a fixed tree through LDS, and lane (0, c) writes the result: no atomics, so the result
-// does not depend on scheduling.  The host picks the widest COLS that still gives at least 256
-// workgroups (one per CU): wide blocks read whole 128-byte lines, narrow ones keep the whole chip
-// busy at layer widths of a few thousand columns (measured on a 4096 x 6144 shard: 1.3 TB/s with
-// 256 threads and 32 columns per workgroup, 2.3 TB/s with 1024 threads).
+// does not depend on scheduling.  The host picks the widest COLS that still gives a quarter (64
+// columns) or an eighth (32 columns) of the 256 CUs a workgroup: wide blocks read whole 128-byte
+// lines, which matters more than filling every CU (measured on a 4096 x 6144 shard: 2.6 TB/s
+// with 96 workgroups of 64 columns, 1.1 TB/s with 384 of 16; 5.2 TB/s on 4096 x 16384 with 256
+// workgroups of 64).  Unrolling the row loop further (8 or 16 loads in flight per thread) was
+// measured slower (2.2 TB/s) on the narrow shard and equal on the wide one.
 #pragma once
 #include "axo_common.hpp"
 
