@@ -368,3 +368,43 @@ def test_very_large_leading_dimensions(ld_elems, what):
     gu.assert_close(oracle, gu.to_host(dW), oracle.fc_wgrad(Xb, dYb), what + " wgrad")
     del keep, held, X, W, dY
     torch.cuda.empty_cache()
+
+
+def test_concurrent_host_threads_on_their_own_streams():
+    """Four host threads enqueue products of different shapes on their own streams at the same time
+    (ctypes releases the interpreter lock during a call, so the library's planners and their
+    per-shape caches are entered concurrently).  Every result is checked against the oracle."""
+    import threading
+    shapes = [(256, 256, 256), (512, 128, 384), (300, 72, 136), (768, 256, 640)]
+    jobs, errors = [], []
+    for i, (M, Kl, Nl) in enumerate(shapes):
+        Xb, Wb, dYb = rand_trio(M, Kl, Nl, 980 + i)
+        t = dict(X=gu.to_dev(Xb), W=gu.to_dev(Wb), dY=gu.to_dev(dYb), Y=gu.empty_dev(M, Nl), dX=gu.empty_dev(M, Kl),
+                 dW=gu.empty_dev(Kl, Nl), stream=torch.cuda.Stream())
+        jobs.append(((M, Kl, Nl), (Xb, Wb, dYb), t))
+    torch.cuda.synchronize()
+
+    def work(shape, t):
+        try:
+            M, Kl, Nl = shape
+            p, st = P(M, Kl, Nl), t["stream"].cuda_stream
+            for _ in range(20):
+                axo.axo_fc_fwd(p, t["X"].data_ptr(), Kl, t["W"].data_ptr(), Nl, None, 0, t["Y"].data_ptr(), Nl,
+                               None, 0, st)
+                axo.axo_fc_dgrad(p, t["dY"].data_ptr(), Nl, t["W"].data_ptr(), Nl, t["dX"].data_ptr(), Kl, None, 0, st)
+                axo.axo_fc_wgrad(p, t["X"].data_ptr(), Kl, t["dY"].data_ptr(), Nl, t["dW"].data_ptr(), Nl, None, 0, st)
+        except Exception as e:  # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(shape, t)) for shape, _, t in jobs]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for shape, (Xb, Wb, dYb), t in jobs:
+        tag = f"thread {shape}"
+        gu.assert_close(oracle, gu.to_host(t["Y"]), oracle.fc_fwd(Xb, Wb), tag + " fwd")
+        gu.assert_close(oracle, gu.to_host(t["dX"]), oracle.fc_dgrad(dYb, Wb), tag + " dgrad")
+        gu.assert_close(oracle, gu.to_host(t["dW"]), oracle.fc_wgrad(Xb, dYb), tag + " wgrad")
