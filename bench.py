@@ -3,8 +3,9 @@
 
 A step is one pass of the hot path over one workload: the forward, dgrad and wgrad local
 products of a 3D-tensor-parallel FC layer shard (for the chain workloads: of every layer), through
-axo_layer_step_grouped (default: one launch over the tiles of all products) or axo_layer_step
-(--step sequential: one launch per product).  Inputs are seeded synthetic bf16 shards, resident
+axo_layer_step (default; the benchmark's layers have buffers of their own, so the library finds one
+dependence level and runs all products in one grouped launch) or axo_layer_step_ordered (--step
+ordered: one launch per product, in program order).  Inputs are seeded synthetic bf16 shards, resident
 in HBM before the timed region.  Prints one JSON line: TFLOP/s of the step (2*M*Kl*Nl flop per
 product), a roofline object for the dominant kernel (HIP-event timed on the launch stream) and the
 CPU oracle timed on a bounded sample of the same workload.
@@ -41,9 +42,9 @@ def main() -> int:
     ap.add_argument("--config", default="cfg2", help="cfg1..cfg5 (default cfg2, the QKV shard)")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time cfg2..cfg5 and gpt20b and report them under 'configs'")
-    ap.add_argument("--step", choices=("sequential", "grouped"), default="grouped",
-                    help="entry point of the timed step: axo_layer_step_grouped (one launch over the tiles of all "
-                         "products; the default) or axo_layer_step (one launch per product, in order)")
+    ap.add_argument("--step", choices=("layer_step", "ordered"), default="layer_step",
+                    help="entry point of the timed step: axo_layer_step (dependence levels, grouped launches; the "
+                         "default) or axo_layer_step_ordered (one launch per product, in program order)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--extras", action="store_true",
                     help="also time the backward-side extras on the largest layer: dgrad through GELU, fp32-accumulating "
@@ -90,7 +91,7 @@ def main() -> int:
         keep.append(ws)
         return layers, objs, keep, flop, ws.data_ptr(), nws
 
-    step_fn = axo.axo_layer_step if args.step == "sequential" else axo.axo_layer_step_grouped
+    step_fn = axo.axo_layer_step_ordered if args.step == "ordered" else axo.axo_layer_step
 
     def time_step(objs, wsp, nws, steps, warmup):
         for _ in range(warmup):
@@ -149,7 +150,7 @@ def main() -> int:
                    "per_op_ms": {k: round(v, 5) for k, v in ops.items()},
                    "per_op_tflops": {k: round(gflop / (v * 1e-3) / 1e12, 2) for k, v in ops.items()}}
     alg_bytes = sum(2 * (L.shard[0] * L.shard[1] + L.shard[1] * L.shard[2] + L.shard[0] * L.shard[2]) for L in layers)
-    if args.step == "grouped" and len(layers) <= 4:
+    if args.step == "layer_step" and len(layers) <= 4:
         # the whole step is ONE launch of gemm_group_kernel: its duration is the step's
         roofline = {"bound": "mfma", "kernel": "gemm_group_kernel (all products of the step)",
                     "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
@@ -173,7 +174,8 @@ def main() -> int:
            "ms_per_step": round(ms, 5), "wall_ms_per_step": round(wall_ms, 5), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
-           "config": {"workload": args.config, "step": args.step, "layers": [
+           "config": {"workload": args.config,
+                      "step": "axo_layer_step_ordered" if args.step == "ordered" else "axo_layer_step", "layers": [
                {"name": L.name, "grid": list(L.grid), "shard_MKN": list(L.shard), "epilogue": L.epilogue}
                for L in layers], "flop_per_step": flop},
            "roofline": roofline}

@@ -184,37 +184,41 @@ typedef struct axo_layer {
 /* Host only.  Largest workspace any single product of the chain needs. */
 size_t axo_layer_step_workspace_bytes(const axo_layer_t *layers, int n_layers);
 
-/* Forward of layers 0..n-1, then for layers n-1..0 the backward pair dgrad, wgrad (Section 4.1
- * issues the dgrad all-reduce before computing wgrad, which fixes this order), all enqueued on one
- * stream without host synchronisation.  The forwards run one after the other, so a layer's Y may
- * be the next layer's X; so do the backward pairs, so a layer's dX may be the previous layer's dY.
- * Inside a pair the two products do not depend on each other (no output of a layer may overlap an
- * input of the same layer) and may share one launch.  All layers are validated before the first
- * launch; on a validation error nothing is enqueued. */
+/* The 3 * n_layers local products of Algorithm 1 for a chain of layers, with the results of this
+ * program order: forward of layers 0..n-1, then for layers n-1..0 dgrad followed by wgrad (Section
+ * 4.1 issues the dgrad all-reduce before computing wgrad, which fixes that order), all enqueued on
+ * one stream without host synchronisation.
+ *
+ * The library does not simply launch them one after the other.  It compares the byte ranges the
+ * products read and write (first to last element of every matrix; pointers are compared, never
+ * dereferenced), gives every product a dependence level (0: conflicts with no earlier product;
+ * otherwise one more than the highest level among the earlier products whose output it reads or
+ * overwrites, or whose input it overwrites), and enqueues level by level.  The products of one
+ * level are independent, and those the tiled kernel takes share grouped launches: the output
+ * tiles of up to 12 products in one grid, most expensive tiles first, so that products too small
+ * to fill the GPU on their own (a 1536 x 1536 shard is 36 tiles for 256 compute units) run side by
+ * side and the level pays one ramp-up and one tail instead of one per product.  A chain whose
+ * layers have buffers of their own is a single level; a layer whose X is the previous layer's Y,
+ * or whose dX is the previous layer's dY, lands on the next level; dgrad and wgrad of a layer
+ * always share a level.  Results are the same, bit for bit, whatever the grouping (every output
+ * element is accumulated in the same order in every tile shape).  Two column blocks interleaved
+ * in one buffer count as overlapping, which only costs concurrency.  Chains of more than 256
+ * layers are not analysed and keep the program order, one product per launch.
+ * All layers are validated before the first launch; on a validation error nothing is enqueued. */
 int axo_layer_step(const axo_layer_t *layers, int n_layers, void *ws, size_t ws_bytes,
                    void *hip_stream);
 
-/* The same products with the same results, bit for bit, as axo_layer_step, for chains whose
- * products are independent of each other: NO output buffer of the call (any layer's Y, dX, dW)
- * may overlap an input buffer of the call (any layer's X, W, bias, dY).  Under that condition the
- * 3 * n_layers local products of Algorithm 1 can run in any order, and the library enqueues them
- * as grouped launches: the output tiles of up to 12 products share one grid, most expensive tiles
- * first, so that products too small to fill the GPU on their own (a 1536 x 1536 shard is 36 tiles
- * for 256 compute units) run side by side and the chain pays one ramp-up and one tail instead of
- * one per product.  Products whose shapes the tiled kernel does not take are launched on their
- * own.  The condition is checked on the host, on the byte ranges the matrices span (first to last
- * element, so two column blocks interleaved in one buffer count as overlapping): a chain that
- * does not meet it, or in which two outputs overlap, is enqueued exactly as axo_layer_step would.
- * Validation, workspace, stream and error behaviour are those of axo_layer_step. */
-int axo_layer_step_grouped(const axo_layer_t *layers, int n_layers, void *ws, size_t ws_bytes,
+/* The same products in the same program order, one launch per product and nothing else: the plain
+ * reading of the order above, kept for comparison (results are bit-identical to axo_layer_step's)
+ * and for timing what the dependence analysis and the grouped launches gain. */
+int axo_layer_step_ordered(const axo_layer_t *layers, int n_layers, void *ws, size_t ws_bytes,
                            void *hip_stream);
 
-/* Host only.  The condition of axo_layer_step_grouped, as that call evaluates it: *independent
- * is set to 1 when no output range of the chain overlaps an input range or another output range
- * (the grouped launches are taken), to 0 otherwise (the call keeps axo_layer_step's order).
- * Pointers are compared, never dereferenced.  Errors: those of axo_layer_step's validation
- * (with ws = NULL, ws_bytes = 0), NULL_PTR (independent). */
-int axo_layer_chain_independent(const axo_layer_t *layers, int n_layers, int *independent);
+/* Host only.  The dependence levels axo_layer_step would use: *n_levels receives their number
+ * (0 for an empty chain) and, when levels is not NULL, levels[0 .. 3 * n_layers) the level of
+ * every product in program order (forward of layers 0..n-1, then dgrad, wgrad of layers n-1..0).
+ * Errors: those of axo_layer_step's validation (with ws = NULL, ws_bytes = 0), NULL_PTR (n_levels). */
+int axo_layer_step_levels(const axo_layer_t *layers, int n_layers, int *n_levels, int *levels);
 
 #ifdef __cplusplus
 }

@@ -92,10 +92,11 @@ def library() -> ctypes.CDLL:
     L.axo_fc_wgrad_acc.restype = i32
     L.axo_bias_grad.argtypes = [PP, vp, i64, vp, i32, vp]
     L.axo_bias_grad.restype = i32
-    L.axo_layer_step_grouped.argtypes = [ctypes.POINTER(Layer), i32, vp, sz, vp]
-    L.axo_layer_step_grouped.restype = i32
-    L.axo_layer_chain_independent.argtypes = [ctypes.POINTER(Layer), i32, ctypes.POINTER(ctypes.c_int)]
-    L.axo_layer_chain_independent.restype = i32
+    L.axo_layer_step_ordered.argtypes = [ctypes.POINTER(Layer), i32, vp, sz, vp]
+    L.axo_layer_step_ordered.restype = i32
+    L.axo_layer_step_levels.argtypes = [ctypes.POINTER(Layer), i32, ctypes.POINTER(ctypes.c_int),
+                                        ctypes.POINTER(ctypes.c_int)]
+    L.axo_layer_step_levels.restype = i32
     _lib = L
     return L
 
@@ -165,17 +166,18 @@ def axo_layer_step(layers: Sequence[Layer], ws: Optional[int] = None, ws_bytes: 
     return _check(rc, "axo_layer_step", check)
 
 
-def axo_layer_step_grouped(layers: Sequence[Layer], ws: Optional[int] = None, ws_bytes: int = 0,
+def axo_layer_step_ordered(layers: Sequence[Layer], ws: Optional[int] = None, ws_bytes: int = 0,
                            stream: Optional[int] = None, check: bool = True) -> int:
-    rc = library().axo_layer_step_grouped(_layer_array(layers), len(layers), ws, ws_bytes, stream)
-    return _check(rc, "axo_layer_step_grouped", check)
+    rc = library().axo_layer_step_ordered(_layer_array(layers), len(layers), ws, ws_bytes, stream)
+    return _check(rc, "axo_layer_step_ordered", check)
 
 
-def axo_layer_chain_independent(layers: Sequence[Layer], check: bool = True) -> Tuple[int, bool]:
-    """(status, whether axo_layer_step_grouped takes the grouped launches for this chain)."""
-    flag = ctypes.c_int(0)
-    rc = library().axo_layer_chain_independent(_layer_array(layers), len(layers), ctypes.byref(flag))
-    return _check(rc, "axo_layer_chain_independent", check), bool(flag.value)
+def axo_layer_step_levels(layers: Sequence[Layer], check: bool = True) -> Tuple[int, int, list]:
+    """(status, number of dependence levels, level of each of the 3 * len(layers) products)."""
+    n = ctypes.c_int(0)
+    lv = (ctypes.c_int * max(1, 3 * len(layers)))()
+    rc = library().axo_layer_step_levels(_layer_array(layers), len(layers), ctypes.byref(n), lv)
+    return _check(rc, "axo_layer_step_levels", check), int(n.value), list(lv)[:3 * len(layers)]
 
 
 def axo_fc_dgrad_act(p: Problem, dY: int, lddy: int, W: int, ldw: int, pre: int, ldpre: int, act: int, dX: int,

@@ -441,11 +441,12 @@ int plan_wgrad_acc(const axo_problem_t* p, const void* X, int64_t ldx, const voi
     return AXO_OK;
 }
 
-// ---- dependence check for the grouped step ---------------------------------------------------
+// ---- dependence analysis of a chain --------------------------------------------------------
 // Byte range [lo, hi) that a matrix argument covers (rows x row_len elements of elem bytes, rows
 // ld elements apart); empty matrices cover nothing.
 struct Range {
     uintptr_t lo, hi;
+    bool overlaps(const Range& o) const { return lo < o.hi && o.lo < hi; }
 };
 bool matrix_range(const void* ptr, int64_t ld, int64_t rows, int64_t row_len, int elem, Range* r) {
     if (!ptr || rows <= 0 || row_len <= 0) return false;
@@ -453,57 +454,92 @@ bool matrix_range(const void* ptr, int64_t ld, int64_t rows, int64_t row_len, in
     r->hi = r->lo + (uintptr_t)(((rows - 1) * ld + row_len) * elem);
     return true;
 }
-void operand_ranges(const Plan& pl, std::vector<Range>* in, std::vector<Range>* out) {
+// What one product reads and writes.  (Ranges, not elements: two column blocks interleaved in one
+// buffer count as overlapping, which only costs concurrency.)
+struct Footprint {
+    Range in[4];
+    int n_in = 0;
+    Range out{0, 0};
+    bool has_out = false;
+    bool conflicts_with_later(const Footprint& later) const {
+        if (has_out) {
+            if (later.has_out && out.overlaps(later.out)) return true;                 // write after write
+            for (int k = 0; k < later.n_in; ++k)
+                if (out.overlaps(later.in[k])) return true;                            // read after write
+        }
+        if (later.has_out)
+            for (int k = 0; k < n_in; ++k)
+                if (in[k].overlaps(later.out)) return true;                            // write after read
+        return false;
+    }
+};
+Footprint footprint(const Plan& pl) {
     const GemmArgs& g = pl.g;
+    Footprint f;
+    if (g.Mo == 0 || g.No == 0) return f;  // nothing is launched for it
     Range r;
     // A(i, r): KC is Mo rows of R elements, MC is R rows of Mo elements; B likewise with No
     if (pl.la == axo::KC ? matrix_range(g.A, g.lda, g.Mo, g.R, 2, &r) : matrix_range(g.A, g.lda, g.R, g.Mo, 2, &r))
-        in->push_back(r);
+        f.in[f.n_in++] = r;
     if (pl.lb == axo::KC ? matrix_range(g.B, g.ldb, g.No, g.R, 2, &r) : matrix_range(g.B, g.ldb, g.R, g.No, 2, &r))
-        in->push_back(r);
-    if (g.add_bias && matrix_range(g.bias, g.No, 1, g.No, 2, &r)) in->push_back(r);
-    if (matrix_range(g.aux, g.ldaux, g.Mo, g.No, 2, &r)) in->push_back(r);
-    if (matrix_range(g.C, g.ldc, g.Mo, g.No, g.epilogue == axo::EPI_ACC_F32 ? 4 : 2, &r)) out->push_back(r);
+        f.in[f.n_in++] = r;
+    if (g.add_bias && matrix_range(g.bias, g.No, 1, g.No, 2, &r)) f.in[f.n_in++] = r;
+    if (matrix_range(g.aux, g.ldaux, g.Mo, g.No, 2, &r)) f.in[f.n_in++] = r;
+    f.has_out = matrix_range(g.C, g.ldc, g.Mo, g.No, g.epilogue == axo::EPI_ACC_F32 ? 4 : 2, &f.out);
+    return f;
 }
-// True when no output of the chain overlaps an input of the chain or another output: the
-// products may then run in any order.  (Ranges, not elements: two interleaved column blocks of one
-// buffer count as overlapping, which only costs the grouping.)
-bool products_independent(const std::vector<Plan>& plans) {
-    std::vector<Range> in, out;
-    for (const Plan& pl : plans) operand_ranges(pl, &in, &out);
-    auto by_lo = [](const Range& a, const Range& b) { return a.lo < b.lo; };
-    std::sort(out.begin(), out.end(), by_lo);
-    for (size_t i = 1; i < out.size(); ++i)
-        if (out[i].lo < out[i - 1].hi) return false;  // sorted and pairwise disjoint from here on
-    for (const Range& r : in) {
-        // first output that ends after r begins
-        auto it = std::upper_bound(out.begin(), out.end(), r.lo, [](uintptr_t v, const Range& o) { return v < o.hi; });
-        if (it != out.end() && it->lo < r.hi) return false;
+// Dependence level of every product of a chain given in program order: 0 when it conflicts with
+// no earlier product, otherwise one more than the highest level among the earlier products it
+// conflicts with.  Products of one level are independent of each other, and every product a
+// given one depends on sits on a lower level, so enqueueing level by level on one stream gives
+// the results of the program order.  The pairwise comparison is quadratic; beyond
+// MAX_ANALYSED products the chain simply keeps its order (level = position).  Returns the
+// number of levels.
+constexpr size_t MAX_ANALYSED = 768;  // 256 layers
+int dependence_levels(const std::vector<Plan>& plans, std::vector<int>* level) {
+    const size_t n = plans.size();
+    level->assign(n, 0);
+    if (n == 0) return 0;
+    if (n > MAX_ANALYSED) {
+        for (size_t j = 0; j < n; ++j) (*level)[j] = (int)j;
+        return (int)n;
     }
-    return true;
+    std::vector<Footprint> fp(n);
+    for (size_t j = 0; j < n; ++j) fp[j] = footprint(plans[j]);
+    int levels = 1;
+    for (size_t j = 1; j < n; ++j) {
+        int lv = 0;
+        for (size_t i = 0; i < j; ++i)
+            if ((*level)[i] >= lv && fp[i].conflicts_with_later(fp[j])) lv = (*level)[i] + 1;
+        (*level)[j] = lv;
+        if (lv + 1 > levels) levels = lv + 1;
+    }
+    return levels;
 }
 
-// the chain in dependence order: see axo_layer_step
-int enqueue_in_order(const std::vector<Plan>& plans, size_t n, hipStream_t st) {
+// Enqueues the products level by level: those of a level that the tiled kernel takes share
+// grouped launches (GROUP_MAX_PRODUCTS per launch), the others get a launch of their own.
+int enqueue_by_level(const std::vector<Plan>& plans, const std::vector<int>& level, int levels, hipStream_t st) {
     int rc = AXO_OK;
-    // forwards one by one, in order: a caller may feed layer i's Y to layer i+1 as X
-    for (size_t i = 0; i < n && i < plans.size() && rc == AXO_OK; ++i) rc = launch(plans[i].g, plans[i].la, plans[i].lb, st);
-    // backward, layer by layer: dgrad and wgrad of one layer never depend on each other (dgrad
-    // reads dY and W and writes dX, wgrad reads X and dY and writes dW), so the pair shares one
-    // launch when the tiled kernel takes both; pairs stay in order (dX of layer i may be the
-    // caller's dY of layer i-1)
-    for (size_t b = n; b + 1 < plans.size() && rc == AXO_OK; b += 2) {
-        const Plan& dg = plans[b];
-        const Plan& wg = plans[b + 1];
-        const bool both = dg.g.Mo > 0 && dg.g.No > 0 && wg.g.Mo > 0 && wg.g.No > 0 && tileable(dg.g, dg.la, dg.lb) &&
-                          tileable(wg.g, wg.la, wg.lb);
-        if (both) {
-            const Plan* pair[2] = {&dg, &wg};
-            rc = launch_group(pair, 2, st);
-        } else {
-            rc = launch(dg.g, dg.la, dg.lb, st);
-            if (rc == AXO_OK) rc = launch(wg.g, wg.la, wg.lb, st);
+    std::vector<const Plan*> group;
+    auto flush = [&]() {
+        if (group.empty() || rc != AXO_OK) return;
+        rc = group.size() == 1 ? launch_tile_layout(group[0]->g, group[0]->la, group[0]->lb, st)
+                               : launch_group(group.data(), (int)group.size(), st);
+        group.clear();
+    };
+    for (int lv = 0; lv < levels && rc == AXO_OK; ++lv) {
+        for (size_t i = 0; i < plans.size() && rc == AXO_OK; ++i) {
+            const Plan& pl = plans[i];
+            if (level[i] != lv || pl.g.Mo == 0 || pl.g.No == 0) continue;
+            if (!tileable(pl.g, pl.la, pl.lb)) {
+                rc = launch_generic(pl.g, pl.la, pl.lb, st);
+                continue;
+            }
+            group.push_back(&pl);
+            if ((int)group.size() == axo::GROUP_MAX_PRODUCTS) flush();
         }
+        flush();
     }
     return rc;
 }
@@ -661,48 +697,33 @@ int axo_layer_step(const axo_layer_t* layers, int n_layers, void* ws, size_t ws_
         std::vector<Plan> plans;
         const int rc = plan_chain(layers, n_layers, ws, ws_bytes, &plans);
         if (rc != AXO_OK) return rc;
-        return enqueue_in_order(plans, (size_t)(n_layers > 0 ? n_layers : 0), static_cast<hipStream_t>(hip_stream));
+        std::vector<int> level;
+        const int levels = dependence_levels(plans, &level);
+        return enqueue_by_level(plans, level, levels, static_cast<hipStream_t>(hip_stream));
     });
 }
 
-int axo_layer_chain_independent(const axo_layer_t* layers, int n_layers, int* independent) {
-    return guarded([&]() -> int {
-        if (!independent) return AXO_ERR_NULL_PTR;
-        std::vector<Plan> plans;
-        const int rc = plan_chain(layers, n_layers, nullptr, 0, &plans);
-        if (rc != AXO_OK) return rc;
-        *independent = products_independent(plans) ? 1 : 0;
-        return AXO_OK;
-    });
-}
-
-int axo_layer_step_grouped(const axo_layer_t* layers, int n_layers, void* ws, size_t ws_bytes, void* hip_stream) {
+int axo_layer_step_ordered(const axo_layer_t* layers, int n_layers, void* ws, size_t ws_bytes, void* hip_stream) {
     return guarded([&]() -> int {
         std::vector<Plan> plans;
         int rc = plan_chain(layers, n_layers, ws, ws_bytes, &plans);
-        if (rc != AXO_OK) return rc;
-        hipStream_t st = static_cast<hipStream_t>(hip_stream);
-        // a chain with a dependence between its products keeps the order of axo_layer_step
-        if (!products_independent(plans)) return enqueue_in_order(plans, (size_t)n_layers, st);
-        std::vector<const Plan*> group;
-        auto flush = [&]() {
-            if (group.empty() || rc != AXO_OK) return;
-            rc = group.size() == 1 ? launch_tile_layout(group[0]->g, group[0]->la, group[0]->lb, st)
-                                   : launch_group(group.data(), (int)group.size(), st);
-            group.clear();
-        };
-        for (size_t i = 0; i < plans.size() && rc == AXO_OK; ++i) {
-            const Plan& pl = plans[i];
-            if (pl.g.Mo == 0 || pl.g.No == 0) continue;
-            if (!tileable(pl.g, pl.la, pl.lb)) {
-                rc = launch_generic(pl.g, pl.la, pl.lb, st);
-                continue;
-            }
-            group.push_back(&pl);
-            if ((int)group.size() == axo::GROUP_MAX_PRODUCTS) flush();
-        }
-        flush();
+        for (size_t i = 0; i < plans.size() && rc == AXO_OK; ++i)
+            rc = launch(plans[i].g, plans[i].la, plans[i].lb, static_cast<hipStream_t>(hip_stream));
         return rc;
+    });
+}
+
+int axo_layer_step_levels(const axo_layer_t* layers, int n_layers, int* n_levels, int* levels) {
+    return guarded([&]() -> int {
+        if (!n_levels) return AXO_ERR_NULL_PTR;
+        std::vector<Plan> plans;
+        const int rc = plan_chain(layers, n_layers, nullptr, 0, &plans);
+        if (rc != AXO_OK) return rc;
+        std::vector<int> level;
+        *n_levels = dependence_levels(plans, &level);
+        if (levels)
+            for (size_t i = 0; i < level.size(); ++i) levels[i] = level[i];
+        return AXO_OK;
     });
 }
 

@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"axo_fc_fwd", "axo_fc_dgrad", "axo_fc_wgrad", "axo_layer_step", "axo_shard_dims",
             "axo_workspace_bytes", "axo_status_string", "axo_version",
-            "axo_layer_step_workspace_bytes", "axo_layer_step_grouped", "axo_layer_chain_independent",
+            "axo_layer_step_workspace_bytes", "axo_layer_step_ordered", "axo_layer_step_levels",
             "axo_comm_rank_configs",
             "axo_comm_layer_time"} <= set(names)
     lib = ctypes.CDLL(axo.library_path())
@@ -153,7 +153,7 @@ def test_empty_shards_need_no_device():
     assert axo.axo_fc_wgrad(pn, A, 32, A, 8, A, 8, check=False) == OK
 
 
-@pytest.mark.parametrize("entry", ["axo_layer_step", "axo_layer_step_grouped"])
+@pytest.mark.parametrize("entry", ["axo_layer_step", "axo_layer_step_ordered"])
 def test_layer_step_validates_whole_chain_first(entry):
     step = getattr(axo, entry)
     # T == 0 and N == 0: none of the three products has an output element, so nothing launches
@@ -172,9 +172,10 @@ def test_layer_step_validates_whole_chain_first(entry):
     assert axo.axo_layer_step_workspace_bytes([good, bad]) >= 0
 
 
-def test_chain_independence_is_decided_on_byte_ranges():
-    """axo_layer_chain_independent (host only; the addresses are made up and never dereferenced):
-    what axo_layer_step_grouped checks before it lets the products of a chain share launches."""
+def test_dependence_levels_are_decided_on_byte_ranges():
+    """axo_layer_step_levels (host only; the addresses are made up and never dereferenced): the
+    dependence analysis by which axo_layer_step decides which products may share a launch.
+    Product order: fwd of layers 0..n-1, then dgrad, wgrad of layers n-1..0."""
     M, K, N = 64, 32, 48
     p = axo.Problem.make((1, 1, 1), (0, 0, 0), M, K, N)
     base = 1 << 20
@@ -182,32 +183,47 @@ def test_chain_independence_is_decided_on_byte_ranges():
     def layer(X, W, Y, dY, dX, dW, ldx=K, ldy=N):
         return axo.Layer(p, 0, 0, X, ldx, W, N, None, Y, ldy, dY, N, dX, K, dW, N)
 
+    def levels(ls):
+        rc, n, lv = axo.axo_layer_step_levels(ls)
+        assert rc == OK and (n == (max(lv) + 1 if lv else 0))
+        return lv
+
     step = 1 << 16  # far more than any of the matrices spans
     a = [base + i * step for i in range(16)]
     l0 = layer(a[0], a[1], a[2], a[3], a[4], a[5])
     l1 = layer(a[6], a[7], a[8], a[9], a[10], a[11])
-    assert axo.axo_layer_chain_independent([]) == (OK, True)
-    assert axo.axo_layer_chain_independent([l0, l1]) == (OK, True)
+    assert axo.axo_layer_step_levels([]) == (OK, 0, [])
+    assert levels([l0]) == [0, 0, 0]
+    # layers with buffers of their own: one level         fwd0 fwd1 dg1 wg1 dg0 wg0
+    assert levels([l0, l1]) == [0, 0, 0, 0, 0, 0]
     # the same weight read by two layers is no dependence
-    assert axo.axo_layer_chain_independent([l0, layer(a[6], a[1], a[8], a[9], a[10], a[11])]) == (OK, True)
-    # layer one reads what layer zero writes
-    assert axo.axo_layer_chain_independent([l0, layer(a[2], a[7], a[8], a[9], a[10], a[11])]) == (OK, False)
-    # layer zero's dY is layer one's dX
-    assert axo.axo_layer_chain_independent([l0, layer(a[6], a[7], a[8], a[9], a[3], a[11])]) == (OK, False)
-    # two layers write the same dW
-    assert axo.axo_layer_chain_independent([l0, layer(a[6], a[7], a[8], a[9], a[10], a[5])]) == (OK, False)
-    # an output that begins on the last byte pair of an input: X spans (M-1)*K + K elements
+    assert levels([l0, layer(a[6], a[1], a[8], a[9], a[10], a[11])]) == [0] * 6
+    # layer one reads what layer zero writes: its fwd and its wgrad (which reads X) wait for fwd 0
+    assert levels([l0, layer(a[2], a[7], a[8], a[9], a[10], a[11])]) == [0, 1, 0, 1, 0, 0]
+    # layer zero's dY is layer one's dX: layer zero's backward pair waits for dgrad 1
+    assert levels([l0, layer(a[6], a[7], a[8], a[9], a[3], a[11])]) == [0, 0, 0, 0, 1, 1]
+    # both at once, the layout of a real two-layer step
+    assert levels([l0, layer(a[2], a[7], a[8], a[9], a[3], a[11])]) == [0, 1, 0, 1, 1, 1]
+    # two layers write the same dW: the later write (wgrad 0) waits for the earlier (wgrad 1)
+    assert levels([l0, layer(a[6], a[7], a[8], a[9], a[10], a[5])]) == [0, 0, 0, 0, 0, 1]
+    # write after read: layer one's Y is the buffer layer zero's forward reads as X; fwd 1 waits for
+    # fwd 0, and wgrad 0, which in program order reads that buffer after fwd 1 has rewritten it, for fwd 1
+    assert levels([l0, layer(a[6], a[7], a[0], a[9], a[10], a[11])]) == [0, 1, 0, 0, 0, 2]
+    # an output that begins on the last 16 bytes of an input: X spans (M - 1) * K + K elements;
+    # fwd writes into what it reads (its own level is 0; wgrad, which reads X, comes after it)
     x_bytes = ((M - 1) * K + K) * 2
-    assert axo.axo_layer_chain_independent([layer(a[0], a[1], a[0] + x_bytes - 16, a[3], a[4], a[5])]) == (OK, False)
-    assert axo.axo_layer_chain_independent([layer(a[0], a[1], a[0] + x_bytes, a[3], a[4], a[5])]) == (OK, True)
+    assert levels([layer(a[0], a[1], a[0] + x_bytes - 16, a[3], a[4], a[5])]) == [0, 0, 1]
+    assert levels([layer(a[0], a[1], a[0] + x_bytes, a[3], a[4], a[5])]) == [0, 0, 0]
     # column blocks interleaved in one buffer (ld twice the row length) count as overlapping
-    assert axo.axo_layer_chain_independent(
-        [layer(a[0], a[1], a[2], a[3], a[4], a[5], ldy=2 * N),
-         layer(a[6], a[7], a[2] + 2 * N, a[9], a[10], a[11], ldy=2 * N)]) == (OK, False)
+    assert levels([layer(a[0], a[1], a[2], a[3], a[4], a[5], ldy=2 * N),
+                   layer(a[6], a[7], a[2] + 2 * N, a[9], a[10], a[11], ldy=2 * N)]) == [0, 1, 0, 0, 0, 0]
+    # a chain of three: each forward waits for the one before
+    l2 = layer(a[8], a[12], a[13], a[14], a[15], base + 16 * step)
+    assert levels([l0, layer(a[2], a[7], a[8], a[9], a[10], a[11]), l2])[:3] == [0, 1, 2]
     # validation comes first
     bad = axo.Layer(p, 0, 0, a[0], K, a[1], N, None, a[2], N, a[3], N, None, K, a[5], N)
-    assert axo.axo_layer_chain_independent([bad], check=False)[0] == NULL_PTR
-    assert axo.library().axo_layer_chain_independent(None, 0, None) == NULL_PTR
+    assert axo.axo_layer_step_levels([bad], check=False)[0] == NULL_PTR
+    assert axo.library().axo_layer_step_levels(None, 0, None, None) == NULL_PTR
 
 
 def test_missing_library_fails_loudly(monkeypatch):

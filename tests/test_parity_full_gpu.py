@@ -1,5 +1,5 @@
 """GPU parity at the benchmark's full shard sizes, in the launch configuration bench.py times
-(contiguous shards, coordinate (0,0,0), axo_layer_step for the chain).  The fp64 oracle computes
+(contiguous shards, coordinate (0,0,0), axo_layer_step for the chain: one dependence level, grouped launches).  The fp64 oracle computes
 a stratified sample of whole output rows (first and last row of every 256-row block plus seeded
 rows inside), so every tile row and, since rows are whole, every tile column is covered."""
 import numpy as np
@@ -77,28 +77,29 @@ def test_chain_equals_single_calls():
         assert torch.equal(Y, t["Y"]) and torch.equal(dX, t["dX"]) and torch.equal(dW, t["dW"])
 
 
-def test_grouped_chain_cfg5_against_oracle():
-    """All 12 products of the chain in one grouped launch, sampled rows against the oracle."""
+def test_ordered_chain_cfg5_against_oracle():
+    """The 12 products of the chain one launch each, in program order, sampled rows against the oracle."""
     layers = syn.configs()["cfg5"]
-    keep = run_chain(layers, axo.axo_layer_step_grouped)
+    keep = run_chain(layers, axo.axo_layer_step_ordered)
     for L, (d, t) in zip(layers, keep):
         check_sampled(L, d, t, 31 + L.layer_index)
 
 
 @pytest.mark.parametrize("cfg", ["cfg2", "cfg5", "gpt20b"])
-def test_grouped_equals_sequential(cfg):
-    """The grouped launch cuts the outputs into other tiles but every element is still reduced in
-    the same order by the same instructions: bit-identical to the sequential chain."""
+def test_scheduled_equals_ordered(cfg):
+    """axo_layer_step finds these chains free of dependences and runs all their products in grouped
+    launches, which cut the outputs into other tiles; every element is still reduced in the same
+    order by the same instructions: bit-identical to one launch per product in program order."""
     layers = syn.configs()[cfg]
     a = run_chain(layers)
-    b = run_chain(layers, axo.axo_layer_step_grouped)
+    b = run_chain(layers, axo.axo_layer_step_ordered)
     for (_, ta), (_, tb) in zip(a, b):
         for k in ("Y", "dX", "dW"):
             assert torch.equal(ta[k], tb[k]), k
 
 
 def test_running_example_gpt20b():
-    """The (2,2,4) shards of the paper's GPT-20B running example (Section 4), sequential chain."""
+    """The (2,2,4) shards of the paper's GPT-20B running example (Section 4) through axo_layer_step."""
     layers = syn.configs()["gpt20b"]
     keep = run_chain(layers)
     for L, (d, t) in zip(layers, keep):

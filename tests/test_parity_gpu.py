@@ -283,7 +283,7 @@ def test_rounding_is_nearest_even():
 
 
 def test_grouped_step_mixed_shapes_against_oracle():
-    """axo_layer_step_grouped on a chain that mixes shapes the tiled kernel takes, shapes it does not
+    """axo_layer_step on an independent chain that mixes shapes the tiled kernel takes, shapes it does not
     (ragged; a product with a 128-row output) and an empty layer: every element against the oracle."""
     shapes = [(256, 256, 256), (300, 72, 136), (256, 128, 384), (512, 384, 640), (0, 64, 64), (768, 256, 1152)]
     layers, keep = [], []
@@ -297,7 +297,8 @@ def test_grouped_step_mixed_shapes_against_oracle():
         layers.append(axo.Layer(P(M, Kl, Nl), epi, 0, t["X"].data_ptr(), Kl, t["W"].data_ptr(), Nl,
                                 t["bias"].data_ptr() if epi else None, t["Y"].data_ptr(), Nl,
                                 t["dY"].data_ptr(), Nl, t["dX"].data_ptr(), Kl, t["dW"].data_ptr(), Nl))
-    axo.axo_layer_step_grouped(layers, None, 0, gu.stream())
+    assert axo.axo_layer_step_levels(layers)[1] == 1
+    axo.axo_layer_step(layers, None, 0, gu.stream())
     torch.cuda.synchronize()
     for i, (Xb, Wb, dYb, bias_b, epi, t) in enumerate(keep):
         if Xb.shape[0] == 0:  # no tokens: dW is an empty sum
@@ -309,12 +310,13 @@ def test_grouped_step_mixed_shapes_against_oracle():
         gu.assert_close(oracle, gu.to_host(t["dW"]), oracle.fc_wgrad(Xb, dYb), tag + " wgrad")
 
 
-@pytest.mark.parametrize("step", ["axo_layer_step", "axo_layer_step_grouped"])
+@pytest.mark.parametrize("step", ["axo_layer_step", "axo_layer_step_ordered"])
 def test_step_with_dependent_layers(step):
     """A chain whose products depend on each other: layer one reads the Y that layer zero writes,
-    and layer zero's dY is the dX that layer one writes.  axo_layer_step runs it in dependence
-    order; axo_layer_step_grouped has to notice the overlap and do the same.  The second product
-    of each dependence is checked against the oracle applied to the bits the first one produced."""
+    and layer zero's dY is the dX that layer one writes.  axo_layer_step has to find the two
+    dependence levels (fwd 0 and dgrad 1 first; then fwd 1, wgrad 1, dgrad 0, wgrad 0) and keep
+    them apart.  The second product of each dependence is checked against the oracle applied to
+    the bits the first one produced."""
     M, K0, N0, N1 = 512, 256, 512, 384
     Xb, W0b, _ = rand_trio(M, K0, N0, 950)
     _, W1b, dY1b = rand_trio(M, N0, N1, 951)
@@ -328,6 +330,7 @@ def test_step_with_dependent_layers(step):
         axo.Layer(P(M, N0, N1), 0, 0, Y0.data_ptr(), N0, W1.data_ptr(), N1, None, Y1.data_ptr(), N1,
                   dY1.data_ptr(), N1, dX1.data_ptr(), N0, dW1.data_ptr(), N1),
     ]
+    assert axo.axo_layer_step_levels(layers)[1:] == (2, [0, 1, 0, 1, 1, 1])
     getattr(axo, step)(layers, None, 0, gu.stream())
     torch.cuda.synchronize()
     Y0b, dX1b = gu.to_host(Y0), gu.to_host(dX1)
