@@ -697,9 +697,15 @@ int axo_layer_step(const axo_layer_t* layers, int n_layers, void* ws, size_t ws_
         std::vector<Plan> plans;
         const int rc = plan_chain(layers, n_layers, ws, ws_bytes, &plans);
         if (rc != AXO_OK) return rc;
+        hipStream_t st = static_cast<hipStream_t>(hip_stream);
+        if (plans.size() > MAX_ANALYSED) {  // not analysed: program order, one product per launch
+            int rc2 = AXO_OK;
+            for (size_t i = 0; i < plans.size() && rc2 == AXO_OK; ++i) rc2 = launch(plans[i].g, plans[i].la, plans[i].lb, st);
+            return rc2;
+        }
         std::vector<int> level;
         const int levels = dependence_levels(plans, &level);
-        return enqueue_by_level(plans, level, levels, static_cast<hipStream_t>(hip_stream));
+        return enqueue_by_level(plans, level, levels, st);
     });
 }
 

@@ -220,6 +220,11 @@ def test_dependence_levels_are_decided_on_byte_ranges():
     # a chain of three: each forward waits for the one before
     l2 = layer(a[8], a[12], a[13], a[14], a[15], base + 16 * step)
     assert levels([l0, layer(a[2], a[7], a[8], a[9], a[10], a[11]), l2])[:3] == [0, 1, 2]
+    # 256 layers (768 products) are still analysed, one more and the chain keeps its order
+    many = [layer(*[base + (7 * i + k) * step for k in range(6)]) for i in range(257)]
+    assert axo.axo_layer_step_levels(many[:256])[1] == 1
+    rc, n, lv = axo.axo_layer_step_levels(many)
+    assert (rc, n) == (OK, 771) and lv == list(range(771))
     # validation comes first
     bad = axo.Layer(p, 0, 0, a[0], K, a[1], N, None, a[2], N, a[3], N, None, K, a[5], N)
     assert axo.axo_layer_step_levels([bad], check=False)[0] == NULL_PTR
