@@ -411,3 +411,35 @@ def test_concurrent_host_threads_on_their_own_streams():
         gu.assert_close(oracle, gu.to_host(t["Y"]), oracle.fc_fwd(Xb, Wb), tag + " fwd")
         gu.assert_close(oracle, gu.to_host(t["dX"]), oracle.fc_dgrad(dYb, Wb), tag + " dgrad")
         gu.assert_close(oracle, gu.to_host(t["dW"]), oracle.fc_wgrad(Xb, dYb), tag + " wgrad")
+
+
+def test_denormals_infinities_and_nans():
+    """Values outside the benchmark's Gaussian inputs.  bf16 denormal inputs are honoured (not
+    flushed: a row of 256 denormals times ones gives their exact sum); an infinity makes its row
+    infinite, and NaN where it meets a zero; a NaN makes its whole row NaN; rows without special
+    values are not disturbed.  The oracle computes the same classes in fp64."""
+    M = Kl = Nl = 256
+    Xb, Wb, _ = rand_trio(M, Kl, Nl, 990)
+    Xb = Xb.copy()
+    Wb = Wb.copy()
+    Xb[0, :] = 0x0040          # 2^-127, a bf16 denormal
+    Wb[:, 0] = 0x3F80          # a column of ones: Y[0, 0] = 256 * 2^-127 = 2^-119 exactly
+    Xb[2, 5] = 0x7F80          # +infinity
+    Wb[5, 2] = 0x0000          # times zero in column 2
+    Xb[3, 7] = 0x7FC0          # NaN
+    X, W, Y = gu.to_dev(Xb), gu.to_dev(Wb), gu.empty_dev(M, Nl)
+    keep = gu.run_fwd(P(M, Kl, Nl), X, W, Y)
+    torch.cuda.synchronize()
+    del keep
+    got = gu.to_host(Y)
+    with np.errstate(invalid="ignore", over="ignore"):
+        ref = oracle.fc_fwd(Xb, Wb)
+    gotf = syn.bf16_bits_to_f64(got)
+    assert got[0, 0] == 0x0400 and ref[0, 0] == 2.0 ** -119
+    finite_rows = np.array([r for r in range(M) if r not in (2, 3)])
+    gu.assert_close(oracle, got[finite_rows], ref[finite_rows], "rows without special values")
+    assert np.isnan(ref[2, 2]) and np.isnan(gotf[2, 2])                      # inf * 0
+    inf_cols = np.isinf(ref[2])
+    assert inf_cols.sum() == Nl - 1
+    assert np.array_equal(np.isinf(gotf[2]), inf_cols) and np.array_equal(np.sign(gotf[2][inf_cols]), np.sign(ref[2][inf_cols]))
+    assert np.isnan(ref[3]).all() and np.isnan(gotf[3]).all()
