@@ -263,3 +263,14 @@ def test_backward_extras_argument_errors():
     assert axo.axo_fc_wgrad_acc(pn, A, 32, A, 8, A, 8, check=False) == OK
     p0 = axo.Problem.make((1, 1, 1), (0, 0, 0), 0, 32, 48)
     assert axo.axo_fc_dgrad_act(p0, A, 48, A, 48, A, 32, 2, A, 32, check=False) == OK
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU's share; asked for more it has to say so and exit non-zero
+    (decided before anything touches a GPU, so this runs anywhere)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "--gpus must be 1" in (r.stdout + r.stderr)
