@@ -30,7 +30,7 @@
  * Ownership: the caller owns all buffers; the library allocates no device memory, keeps no pointer after
  * a call returns, and only enqueues work on the caller's HIP stream (no device synchronisation,
  * no host read-back).  Buffers must stay valid until the stream has executed the call.
- * Outputs must not alias inputs.  A matrix with no elements (a zero shard dimension) is never
+ * The output of a product must not overlap an input of the same product.  A matrix with no elements (a zero shard dimension) is never
  * dereferenced: its pointer may be NULL and its leading dimension is not checked.
  *
  * Errors: every function returns an int status, 0 on success, negative on error; nothing throws
@@ -119,18 +119,22 @@ size_t axo_workspace_bytes(const axo_problem_t *p, int op);
  * epilogue == AXO_EPI_NONE.  ws / ws_bytes: device workspace of at least
  * axo_workspace_bytes(p, AXO_OP_FWD) bytes (may be NULL when that is 0).  hip_stream: a
  * hipStream_t (NULL = the default stream).  A shard with M, Kl or Nl == 0 is valid: with
- * Kl == 0 the output is epilogue(0); with M or Nl == 0 nothing is written. */
+ * Kl == 0 the output is epilogue(0); with M or Nl == 0 nothing is written.
+ * Errors: those of axo_shard_dims; BAD_EPILOGUE (unknown epilogue, or one with bias == NULL);
+ * NULL_PTR, BAD_LD, MISALIGNED for X, W, Y, bias; WORKSPACE; HIP; NO_MEMORY. */
 int axo_fc_fwd(const axo_problem_t *p, const void *X, int64_t ldx, const void *W, int64_t ldw,
                const void *bias, int epilogue, void *Y, int64_t ldy,
                void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Backward data gradient  dX[M x Kl] = dY[M x Nl] . W[Kl x Nl]^T.
- * lddy >= Nl, ldw >= Nl, lddx >= Kl; same alignment rules; workspace per AXO_OP_DGRAD. */
+ * lddy >= Nl, ldw >= Nl, lddx >= Kl; same alignment rules; workspace per AXO_OP_DGRAD.
+ * Errors: as axo_fc_fwd, without BAD_EPILOGUE. */
 int axo_fc_dgrad(const axo_problem_t *p, const void *dY, int64_t lddy, const void *W, int64_t ldw,
                  void *dX, int64_t lddx, void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Backward weight gradient  dW[Kl x Nl] = X[M x Kl]^T . dY[M x Nl].
- * ldx >= Kl, lddy >= Nl, lddw >= Nl; same alignment rules; workspace per AXO_OP_WGRAD. */
+ * ldx >= Kl, lddy >= Nl, lddw >= Nl; same alignment rules; workspace per AXO_OP_WGRAD.
+ * Errors: as axo_fc_fwd, without BAD_EPILOGUE. */
 int axo_fc_wgrad(const axo_problem_t *p, const void *X, int64_t ldx, const void *dY, int64_t lddy,
                  void *dW, int64_t lddw, void *ws, size_t ws_bytes, void *hip_stream);
 
