@@ -193,7 +193,14 @@ def main() -> int:
                        args.steps, args.warmup)
         t_bg = time_op(lambda: axo.axo_bias_grad(o.p, o.dY, o.lddy, db.data_ptr(), 0, st), args.steps, args.warmup)
         bg_bytes = 2 * M * Nl + 4 * Nl
+        # the whole local step of that layer with all extras, through the scheduled chain entry point
+        ext = [axo.LayerExt.make(o, pre=pre.data_ptr(), ldpre=Kl, act_below=axo.AXO_EPI_BIAS_GELU_TANH,
+                                 dW32=dW32.data_ptr(), lddw32=Nl, db=db.data_ptr(), accumulate_db=0)]
+        t_ext = time_op(lambda: axo.axo_layer_step_ext(ext, wsp, nws, st), args.steps, args.warmup)
         out["extras"] = {
+            "layer_step_ext": {"ms": round(t_ext, 5), "tflops": round(3 * gflop / (t_ext * 1e-3) / 1e12, 2),
+                               "what": "fwd + dgrad through GELU + fp32-accumulating wgrad + bias gradient, one call",
+                               "separate_calls_ms": round(ops["fwd"] + t_da + t_wa + t_bg, 5)},
             "layer": L.name,
             "dgrad_gelu_tanh": {"ms": round(t_da, 5), "tflops": round(gflop / (t_da * 1e-3) / 1e12, 2),
                                 "plain_dgrad_ms": round(ops["dgrad"], 5)},

@@ -224,6 +224,37 @@ int axo_layer_step_ordered(const axo_layer_t *layers, int n_layers, void *ws, si
  * Errors: those of axo_layer_step's validation (with ws = NULL, ws_bytes = 0), NULL_PTR (n_levels). */
 int axo_layer_step_levels(const axo_layer_t *layers, int n_layers, int *n_levels, int *levels);
 
+/* ---- A layer's whole local step, backward-side extras included ----------------------------
+ * One FC layer as axo_layer_t describes it, plus what its backward pass does besides the two
+ * products (see axo_fc_dgrad_act, axo_fc_wgrad_acc, axo_bias_grad for the operations and their
+ * argument rules).  Every extra is optional and switched on by a non-NULL pointer:
+ *   pre   != NULL: dX = (dY . W^T) * act'(pre), act = act_below (AXO_EPI_BIAS_GELU_TANH or _ERF);
+ *                  with pre == NULL act_below must be 0 and dgrad is the plain product;
+ *   dW32  != NULL: the weight gradient is accumulated, unrounded, into this fp32 matrix
+ *                  (dW32 += X^T . dY, lddw32 in fp32 elements) and layer.dW is not written
+ *                  (it may be NULL);
+ *   db    != NULL: db[Nl] = column sums of dY in fp32 (db += ... when accumulate_db == 1). */
+typedef struct axo_layer_ext {
+    axo_layer_t layer;
+    const void *pre;  int64_t ldpre;   /* [M x Kl] bf16 pre-activation of the layer below, or NULL */
+    float *dW32;      int64_t lddw32;  /* [Kl x Nl] fp32 master gradient, or NULL                  */
+    float *db;                         /* [Nl] fp32 bias gradient, or NULL                         */
+    int32_t act_below;                 /* axo_epilogue_t, see above                                */
+    int32_t accumulate_db;             /* 0 or 1                                                   */
+} axo_layer_ext_t;
+
+/* axo_layer_step for layers with extras.  Program order: forward of layers 0..n-1, then for
+ * layers n-1..0 dgrad, wgrad, bias gradient.  Scheduling is that of axo_layer_step: dependence
+ * levels from the byte ranges read and written (an accumulating call reads what it writes),
+ * independent products of a level in grouped launches (the fused variants take part in them: they
+ * differ from the plain products only in their epilogue), bias gradients as launches of their
+ * own within their level.  Results are bit-identical to the single calls in program order.
+ * Errors: those of the single calls; BAD_EPILOGUE (act_below not a GELU kind with pre != NULL, or
+ * not 0 with pre == NULL); BAD_ARG (accumulate_db not 0/1, a reserved field not 0, n_layers < 0 or
+ * > 4096).  On a validation error nothing is enqueued. */
+int axo_layer_step_ext(const axo_layer_ext_t *layers, int n_layers, void *ws, size_t ws_bytes,
+                       void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

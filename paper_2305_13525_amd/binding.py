@@ -49,6 +49,19 @@ class Layer(ctypes.Structure):
                 ("dW", ctypes.c_void_p), ("lddw", ctypes.c_int64)]
 
 
+class LayerExt(ctypes.Structure):
+    """axo_layer_ext_t: a layer plus the optional backward-side extras of axo_layer_step_ext."""
+    _fields_ = [("layer", Layer),
+                ("pre", ctypes.c_void_p), ("ldpre", ctypes.c_int64),
+                ("dW32", ctypes.c_void_p), ("lddw32", ctypes.c_int64),
+                ("db", ctypes.c_void_p),
+                ("act_below", ctypes.c_int32), ("accumulate_db", ctypes.c_int32)]
+
+    @classmethod
+    def make(cls, layer: Layer, pre=None, ldpre=0, act_below=0, dW32=None, lddw32=0, db=None, accumulate_db=0):
+        return cls(layer, pre, ldpre, dW32, lddw32, db, act_below, accumulate_db)
+
+
 _lib: Optional[ctypes.CDLL] = None
 
 
@@ -92,6 +105,8 @@ def library() -> ctypes.CDLL:
     L.axo_fc_wgrad_acc.restype = i32
     L.axo_bias_grad.argtypes = [PP, vp, i64, vp, i32, vp]
     L.axo_bias_grad.restype = i32
+    L.axo_layer_step_ext.argtypes = [ctypes.POINTER(LayerExt), i32, vp, sz, vp]
+    L.axo_layer_step_ext.restype = i32
     L.axo_layer_step_ordered.argtypes = [ctypes.POINTER(Layer), i32, vp, sz, vp]
     L.axo_layer_step_ordered.restype = i32
     L.axo_layer_step_levels.argtypes = [ctypes.POINTER(Layer), i32, ctypes.POINTER(ctypes.c_int),
@@ -164,6 +179,15 @@ def axo_layer_step(layers: Sequence[Layer], ws: Optional[int] = None, ws_bytes: 
                    stream: Optional[int] = None, check: bool = True) -> int:
     rc = library().axo_layer_step(_layer_array(layers), len(layers), ws, ws_bytes, stream)
     return _check(rc, "axo_layer_step", check)
+
+
+def axo_layer_step_ext(layers: Sequence[LayerExt], ws: Optional[int] = None, ws_bytes: int = 0,
+                       stream: Optional[int] = None, check: bool = True) -> int:
+    arr = (LayerExt * max(1, len(layers)))()
+    for i, l in enumerate(layers):
+        arr[i] = l
+    rc = library().axo_layer_step_ext(arr, len(layers), ws, ws_bytes, stream)
+    return _check(rc, "axo_layer_step_ext", check)
 
 
 def axo_layer_step_ordered(layers: Sequence[Layer], ws: Optional[int] = None, ws_bytes: int = 0,

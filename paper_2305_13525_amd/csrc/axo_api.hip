@@ -281,10 +281,14 @@ int check_workspace(const axo_problem_t* p, int op, const void* ws, size_t ws_by
     return AXO_OK;
 }
 
-// Validated, launch-ready description of one product.
+// Validated, launch-ready description of one unit of work of a chain: a product (the usual
+// case) or a bias gradient.
 struct Plan {
-    GemmArgs g;
-    int la, lb;
+    GemmArgs g{};
+    int la = 0, lb = 0;
+    bool bias_grad = false;   // bg is valid instead of g
+    axo::BiasGradArgs bg{};
+    bool nothing_to_do() const { return bias_grad ? bg.Nl == 0 : (g.Mo == 0 || g.No == 0); }
 };
 
 // One launch over the tiles of all given products (each tileable and non-empty, at most
@@ -385,6 +389,43 @@ int plan_wgrad(const axo_problem_t* p, const void* X, int64_t ldx, const void* d
     return AXO_OK;
 }
 
+int plan_bias_grad(const axo_problem_t* p, const void* dY, int64_t lddy, float* db, int accumulate, Plan* out) {
+    Shard s;
+    int rc = derive_shard(p, &s);
+    if (rc) return rc;
+    if (accumulate != 0 && accumulate != 1) return AXO_ERR_BAD_ARG;
+    if ((rc = check_matrix(dY, lddy, s.M, s.Nl))) return rc;
+    out->bias_grad = true;
+    out->bg.dY = static_cast<const axo::bf16_t*>(dY);
+    out->bg.lddy = lddy;
+    out->bg.db = db;
+    out->bg.M = (int)s.M;
+    out->bg.Nl = (int)s.Nl;
+    out->bg.accumulate = accumulate;
+    if (s.Nl == 0) return AXO_OK;
+    if (!db) return AXO_ERR_NULL_PTR;
+    if (reinterpret_cast<uintptr_t>(db) & 3u) return AXO_ERR_MISALIGNED;
+    return AXO_OK;
+}
+
+int launch_bias_grad(const axo::BiasGradArgs& g, hipStream_t st) {
+    if (g.Nl == 0) return AXO_OK;
+    auto blocks = [&](int cols) { return (unsigned)((g.Nl + cols - 1) / cols); };
+    // the widest column block that still gives a quarter (an eighth) of the CUs a workgroup
+    if (blocks(64) >= (unsigned)NUM_CU / 4)
+        hipLaunchKernelGGL(axo::bias_grad_kernel<64>, dim3(blocks(64)), dim3(axo::BG_THREADS), 0, st, g);
+    else if (blocks(32) >= (unsigned)NUM_CU / 8)
+        hipLaunchKernelGGL(axo::bias_grad_kernel<32>, dim3(blocks(32)), dim3(axo::BG_THREADS), 0, st, g);
+    else
+        hipLaunchKernelGGL(axo::bias_grad_kernel<16>, dim3(blocks(16)), dim3(axo::BG_THREADS), 0, st, g);
+    return hipGetLastError() == hipSuccess ? AXO_OK : AXO_ERR_HIP;
+}
+
+// one unit of work on its own
+int launch_plan(const Plan& pl, hipStream_t st) {
+    return pl.bias_grad ? launch_bias_grad(pl.bg, st) : launch(pl.g, pl.la, pl.lb, st);
+}
+
 // Validates a chain and lists its products in the order of Section 4.1: forwards of layers
 // 0..n-1, then for layers n-1..0 dgrad followed by wgrad.  Nothing is launched here, so a chain
 // with a malformed product enqueues nothing.
@@ -441,6 +482,49 @@ int plan_wgrad_acc(const axo_problem_t* p, const void* X, int64_t ldx, const voi
     return AXO_OK;
 }
 
+// The chain of axo_layer_step_ext: 3 or 4 units per layer, in program order.
+int plan_chain_ext(const axo_layer_ext_t* layers, int n_layers, void* ws, size_t ws_bytes, std::vector<Plan>* out) {
+    if (n_layers < 0) return AXO_ERR_BAD_ARG;
+    if (n_layers == 0) return AXO_OK;
+    if (!layers) return AXO_ERR_NULL_PTR;
+    if (n_layers > 4096) return AXO_ERR_BAD_ARG;
+    out->clear();
+    out->resize((size_t)n_layers);  // the forwards; the backward units are appended in order
+    for (int i = 0; i < n_layers; ++i) {
+        const axo_layer_t& L = layers[i].layer;
+        if (L.reserved != 0) return AXO_ERR_BAD_ARG;
+        const int rc = plan_fwd(&L.p, L.X, L.ldx, L.W, L.ldw, L.bias, L.epilogue, L.Y, L.ldy, ws, ws_bytes, &(*out)[i]);
+        if (rc) return rc;
+    }
+    for (int i = n_layers - 1; i >= 0; --i) {
+        const axo_layer_ext_t& E = layers[i];
+        const axo_layer_t& L = E.layer;
+        if (E.accumulate_db != 0 && E.accumulate_db != 1) return AXO_ERR_BAD_ARG;
+        Plan pl;
+        int rc;
+        if (E.pre) {
+            rc = plan_dgrad_act(&L.p, L.dY, L.lddy, L.W, L.ldw, E.pre, E.ldpre, E.act_below, L.dX, L.lddx, ws, ws_bytes, &pl);
+        } else {
+            if (E.act_below != 0) return AXO_ERR_BAD_EPILOGUE;
+            rc = plan_dgrad(&L.p, L.dY, L.lddy, L.W, L.ldw, L.dX, L.lddx, ws, ws_bytes, &pl);
+        }
+        if (rc) return rc;
+        out->push_back(pl);
+        pl = Plan();
+        rc = E.dW32 ? plan_wgrad_acc(&L.p, L.X, L.ldx, L.dY, L.lddy, E.dW32, E.lddw32, ws, ws_bytes, &pl)
+                    : plan_wgrad(&L.p, L.X, L.ldx, L.dY, L.lddy, L.dW, L.lddw, ws, ws_bytes, &pl);
+        if (rc) return rc;
+        out->push_back(pl);
+        if (E.db) {
+            pl = Plan();
+            rc = plan_bias_grad(&L.p, L.dY, L.lddy, E.db, E.accumulate_db, &pl);
+            if (rc) return rc;
+            out->push_back(pl);
+        }
+    }
+    return AXO_OK;
+}
+
 // ---- dependence analysis of a chain --------------------------------------------------------
 // Byte range [lo, hi) that a matrix argument covers (rows x row_len elements of elem bytes, rows
 // ld elements apart); empty matrices cover nothing.
@@ -476,8 +560,13 @@ struct Footprint {
 Footprint footprint(const Plan& pl) {
     const GemmArgs& g = pl.g;
     Footprint f;
-    if (g.Mo == 0 || g.No == 0) return f;  // nothing is launched for it
+    if (pl.nothing_to_do()) return f;  // nothing is launched for it
     Range r;
+    if (pl.bias_grad) {  // reads dY, writes (or updates) db
+        if (matrix_range(pl.bg.dY, pl.bg.lddy, pl.bg.M, pl.bg.Nl, 2, &r)) f.in[f.n_in++] = r;
+        f.has_out = matrix_range(pl.bg.db, pl.bg.Nl, 1, pl.bg.Nl, 4, &f.out);
+        return f;
+    }
     // A(i, r): KC is Mo rows of R elements, MC is R rows of Mo elements; B likewise with No
     if (pl.la == axo::KC ? matrix_range(g.A, g.lda, g.Mo, g.R, 2, &r) : matrix_range(g.A, g.lda, g.R, g.Mo, 2, &r))
         f.in[f.n_in++] = r;
@@ -531,7 +620,11 @@ int enqueue_by_level(const std::vector<Plan>& plans, const std::vector<int>& lev
     for (int lv = 0; lv < levels && rc == AXO_OK; ++lv) {
         for (size_t i = 0; i < plans.size() && rc == AXO_OK; ++i) {
             const Plan& pl = plans[i];
-            if (level[i] != lv || pl.g.Mo == 0 || pl.g.No == 0) continue;
+            if (level[i] != lv || pl.nothing_to_do()) continue;
+            if (pl.bias_grad) {
+                rc = launch_bias_grad(pl.bg, st);
+                continue;
+            }
             if (!tileable(pl.g, pl.la, pl.lb)) {
                 rc = launch_generic(pl.g, pl.la, pl.lb, st);
                 continue;
@@ -542,6 +635,18 @@ int enqueue_by_level(const std::vector<Plan>& plans, const std::vector<int>& lev
         flush();
     }
     return rc;
+}
+
+// A validated chain, scheduled by dependence level.
+int enqueue_scheduled(const std::vector<Plan>& plans, hipStream_t st) {
+    if (plans.size() > MAX_ANALYSED) {  // not analysed: program order, one unit per launch
+        int rc = AXO_OK;
+        for (size_t i = 0; i < plans.size() && rc == AXO_OK; ++i) rc = launch_plan(plans[i], st);
+        return rc;
+    }
+    std::vector<int> level;
+    const int levels = dependence_levels(plans, &level);
+    return enqueue_by_level(plans, level, levels, st);
 }
 
 // No exception leaves the library: the planners keep their lists and caches in standard
@@ -654,31 +759,10 @@ int axo_fc_wgrad_acc(const axo_problem_t* p, const void* X, int64_t ldx, const v
 }
 
 int axo_bias_grad(const axo_problem_t* p, const void* dY, int64_t lddy, float* db, int accumulate, void* hip_stream) {
-    Shard s;
-    int rc = derive_shard(p, &s);
+    Plan pl;
+    const int rc = plan_bias_grad(p, dY, lddy, db, accumulate, &pl);
     if (rc) return rc;
-    if (accumulate != 0 && accumulate != 1) return AXO_ERR_BAD_ARG;
-    if ((rc = check_matrix(dY, lddy, s.M, s.Nl))) return rc;
-    if (s.Nl == 0) return AXO_OK;
-    if (!db) return AXO_ERR_NULL_PTR;
-    if (reinterpret_cast<uintptr_t>(db) & 3u) return AXO_ERR_MISALIGNED;
-    axo::BiasGradArgs g;
-    g.dY = static_cast<const axo::bf16_t*>(dY);
-    g.lddy = lddy;
-    g.db = db;
-    g.M = (int)s.M;
-    g.Nl = (int)s.Nl;
-    g.accumulate = accumulate;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    auto blocks = [&](int cols) { return (unsigned)((s.Nl + cols - 1) / cols); };
-    // the widest column block that still gives every CU a workgroup
-    if (blocks(64) >= (unsigned)NUM_CU / 4)
-        hipLaunchKernelGGL(axo::bias_grad_kernel<64>, dim3(blocks(64)), dim3(axo::BG_THREADS), 0, st, g);
-    else if (blocks(32) >= (unsigned)NUM_CU / 8)
-        hipLaunchKernelGGL(axo::bias_grad_kernel<32>, dim3(blocks(32)), dim3(axo::BG_THREADS), 0, st, g);
-    else
-        hipLaunchKernelGGL(axo::bias_grad_kernel<16>, dim3(blocks(16)), dim3(axo::BG_THREADS), 0, st, g);
-    return hipGetLastError() == hipSuccess ? AXO_OK : AXO_ERR_HIP;
+    return launch_bias_grad(pl.bg, static_cast<hipStream_t>(hip_stream));
 }
 
 size_t axo_layer_step_workspace_bytes(const axo_layer_t* layers, int n_layers) {
@@ -697,15 +781,16 @@ int axo_layer_step(const axo_layer_t* layers, int n_layers, void* ws, size_t ws_
         std::vector<Plan> plans;
         const int rc = plan_chain(layers, n_layers, ws, ws_bytes, &plans);
         if (rc != AXO_OK) return rc;
-        hipStream_t st = static_cast<hipStream_t>(hip_stream);
-        if (plans.size() > MAX_ANALYSED) {  // not analysed: program order, one product per launch
-            int rc2 = AXO_OK;
-            for (size_t i = 0; i < plans.size() && rc2 == AXO_OK; ++i) rc2 = launch(plans[i].g, plans[i].la, plans[i].lb, st);
-            return rc2;
-        }
-        std::vector<int> level;
-        const int levels = dependence_levels(plans, &level);
-        return enqueue_by_level(plans, level, levels, st);
+        return enqueue_scheduled(plans, static_cast<hipStream_t>(hip_stream));
+    });
+}
+
+int axo_layer_step_ext(const axo_layer_ext_t* layers, int n_layers, void* ws, size_t ws_bytes, void* hip_stream) {
+    return guarded([&]() -> int {
+        std::vector<Plan> plans;
+        const int rc = plan_chain_ext(layers, n_layers, ws, ws_bytes, &plans);
+        if (rc != AXO_OK) return rc;
+        return enqueue_scheduled(plans, static_cast<hipStream_t>(hip_stream));
     });
 }
 
@@ -714,7 +799,7 @@ int axo_layer_step_ordered(const axo_layer_t* layers, int n_layers, void* ws, si
         std::vector<Plan> plans;
         int rc = plan_chain(layers, n_layers, ws, ws_bytes, &plans);
         for (size_t i = 0; i < plans.size() && rc == AXO_OK; ++i)
-            rc = launch(plans[i].g, plans[i].la, plans[i].lb, static_cast<hipStream_t>(hip_stream));
+            rc = launch_plan(plans[i], static_cast<hipStream_t>(hip_stream));
         return rc;
     });
 }

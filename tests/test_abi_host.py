@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"axo_fc_fwd", "axo_fc_dgrad", "axo_fc_wgrad", "axo_layer_step", "axo_shard_dims",
             "axo_workspace_bytes", "axo_status_string", "axo_version",
-            "axo_layer_step_workspace_bytes", "axo_layer_step_ordered", "axo_layer_step_levels",
+            "axo_layer_step_workspace_bytes", "axo_layer_step_ordered", "axo_layer_step_levels", "axo_layer_step_ext",
             "axo_comm_rank_configs",
             "axo_comm_layer_time"} <= set(names)
     lib = ctypes.CDLL(axo.library_path())
@@ -44,6 +44,8 @@ def test_struct_layout_matches_header():
     assert axo.Problem.T.offset == 24 and axo.Problem.transposed.offset == 48
     assert ctypes.sizeof(axo.Layer) == 56 + 8 + 13 * 8
     assert axo.Layer.X.offset == 64 and axo.Layer.bias.offset == 96 and axo.Layer.dW.offset == 152
+    assert ctypes.sizeof(axo.LayerExt) == ctypes.sizeof(axo.Layer) + 5 * 8 + 8
+    assert axo.LayerExt.pre.offset == 168 and axo.LayerExt.db.offset == 200 and axo.LayerExt.act_below.offset == 208
 
 
 def test_status_strings():
@@ -274,3 +276,27 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0
     assert "--gpus must be 1" in (r.stdout + r.stderr)
+
+
+def test_layer_step_ext_validation():
+    """The extras of axo_layer_step_ext are validated like the single calls, before any launch."""
+    p = axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 48)
+    base = axo.Layer(p, 0, 0, A, 32, A, 48, None, A, 48, A, 48, A, 32, A, 48)
+    ext = axo.LayerExt.make
+    step = lambda ls: axo.axo_layer_step_ext(ls, check=False)
+    assert step([]) == OK
+    assert step([ext(base, act_below=2)]) == BAD_EPI                        # an activation without its pre-activation
+    assert step([ext(base, pre=A, ldpre=32, act_below=0)]) == BAD_EPI       # a pre-activation without an activation
+    assert step([ext(base, pre=A, ldpre=32, act_below=1)]) == BAD_EPI       # bias alone is no activation
+    assert step([ext(base, pre=A, ldpre=24, act_below=2)]) == BAD_LD
+    assert step([ext(base, dW32=A, lddw32=40)]) == BAD_LD
+    assert step([ext(base, dW32=A, lddw32=50)]) == MISALIGNED
+    assert step([ext(base, db=A + 2)]) == MISALIGNED
+    assert step([ext(base, db=A, accumulate_db=2)]) == BAD_ARG
+    no_dw = axo.Layer(p, 0, 0, A, 32, A, 48, None, A, 48, A, 48, A, 32, None, 48)
+    assert step([ext(no_dw)]) == NULL_PTR                                    # plain wgrad needs layer.dW ...
+    empty = axo.Problem.make((1, 1, 1), (0, 0, 0), 0, 32, 0)                # (nothing to launch: valid anywhere)
+    nothing = axo.Layer(empty, 0, 0, A, 32, A, 8, None, A, 8, A, 8, A, 32, None, 8)
+    assert step([ext(nothing, dW32=A, lddw32=8)]) == OK                      # ... the fp32 one does not
+    assert axo.library().axo_layer_step_ext(None, 1, None, 0, None) == NULL_PTR
+    assert axo.library().axo_layer_step_ext(None, -1, None, 0, None) == BAD_ARG

@@ -114,3 +114,75 @@ def test_bias_grad_in_place_columns():
     axo.axo_bias_grad(axo.Problem.make((1, 4, 1), (0, 2, 0), M, 8, N), dY[:, 512:].data_ptr(), N, db.data_ptr(), 0, gu.stream())
     torch.cuda.synchronize()
     assert np.max(np.abs(db.cpu().numpy() - oracle.bias_grad(dYb[:, 512:768]))) <= 1e-3
+
+
+def test_layer_step_ext_against_single_calls_and_oracle():
+    """axo_layer_step_ext on three layers with buffers of their own: a plain layer, one with all
+    three extras (dgrad through the tanh GELU, fp32 weight-gradient accumulation, bias gradient) and
+    one with the erf GELU and an accumulating bias gradient.  The chain is one dependence level, so
+    the fused products share a grouped launch with the plain ones.  Every output is checked against
+    the oracle, and bit for bit against the single calls."""
+    shapes = [(512, 256, 384), (768, 256, 640), (256, 384, 256)]
+    rng = np.random.default_rng(31)
+    keep, layers = [], []
+    for i, (M, Kl, Nl) in enumerate(shapes):
+        Xb, Wb, dYb = (syn.normal_bf16(40 + i, 0, (M, Kl), 1.0), syn.normal_bf16(40 + i, 1, (Kl, Nl), 0.05),
+                       syn.normal_bf16(40 + i, 2, (M, Nl), 1.0))
+        Pb = syn.normal_bf16(40 + i, 3, (M, Kl), 1.5)
+        base32 = (rng.standard_normal((Kl, Nl)) * 30.0).astype(np.float32)
+        basedb = (rng.standard_normal(Nl) * 5.0).astype(np.float32)
+        t = dict(X=gu.to_dev(Xb), W=gu.to_dev(Wb), dY=gu.to_dev(dYb), pre=gu.to_dev(Pb), Y=gu.empty_dev(M, Nl),
+                 dX=gu.empty_dev(M, Kl), dW=gu.empty_dev(Kl, Nl), dW32=torch.from_numpy(base32.copy()).to("cuda:0"),
+                 db=torch.from_numpy(basedb.copy()).to("cuda:0"))
+        L = axo.Layer(P(M, Kl, Nl), 0, 0, t["X"].data_ptr(), Kl, t["W"].data_ptr(), Nl, None, t["Y"].data_ptr(), Nl,
+                      t["dY"].data_ptr(), Nl, t["dX"].data_ptr(), Kl, t["dW"].data_ptr(), Nl)
+        if i == 0:
+            E = axo.LayerExt.make(L)
+        elif i == 1:
+            E = axo.LayerExt.make(L, pre=t["pre"].data_ptr(), ldpre=Kl, act_below=axo.AXO_EPI_BIAS_GELU_TANH,
+                                  dW32=t["dW32"].data_ptr(), lddw32=Nl, db=t["db"].data_ptr(), accumulate_db=0)
+        else:
+            E = axo.LayerExt.make(L, pre=t["pre"].data_ptr(), ldpre=Kl, act_below=axo.AXO_EPI_BIAS_GELU_ERF,
+                                  db=t["db"].data_ptr(), accumulate_db=1)
+        layers.append(E)
+        keep.append((Xb, Wb, dYb, Pb, base32, basedb, t))
+    axo.axo_layer_step_ext(layers, None, 0, gu.stream())
+    torch.cuda.synchronize()
+    for i, ((M, Kl, Nl), (Xb, Wb, dYb, Pb, base32, basedb, t)) in enumerate(zip(shapes, keep)):
+        p, tag = P(M, Kl, Nl), f"layer {i}"
+        gu.assert_close(oracle, gu.to_host(t["Y"]), oracle.fc_fwd(Xb, Wb), tag + " fwd")
+        act = {1: axo.AXO_EPI_BIAS_GELU_TANH, 2: axo.AXO_EPI_BIAS_GELU_ERF}.get(i)
+        ref_dx = oracle.fc_dgrad_act(dYb, Wb, Pb, act) if act else oracle.fc_dgrad(dYb, Wb)
+        gu.assert_close(oracle, gu.to_host(t["dX"]), ref_dx, tag + " dgrad")
+        ref_dw = oracle.fc_wgrad(Xb, dYb)
+        if i == 1:   # accumulated in fp32 on top of the initial contents; the bf16 dW was not written
+            got = t["dW32"].cpu().numpy().astype(np.float64)
+            assert np.max(np.abs(got - (base32.astype(np.float64) + ref_dw))) <= 2e-5 * (np.sqrt(M) + 30.0)
+            assert (gu.to_host(t["dW"]) == 0x7FC0).all()
+        else:
+            gu.assert_close(oracle, gu.to_host(t["dW"]), ref_dw, tag + " wgrad")
+            assert np.array_equal(t["dW32"].cpu().numpy(), base32)
+        ref_db = oracle.bias_grad(dYb)
+        tol = 4e-6 * np.sqrt(M) * 4 + 1e-5
+        got_db = t["db"].cpu().numpy().astype(np.float64)
+        if i == 0:
+            assert np.array_equal(t["db"].cpu().numpy(), basedb)
+        elif i == 1:
+            assert np.max(np.abs(got_db - ref_db)) <= tol
+        else:
+            assert np.max(np.abs(got_db - (basedb.astype(np.float64) + ref_db))) <= tol
+        # the single calls give the same bits
+        Y2, dX2 = gu.empty_dev(M, Nl), gu.empty_dev(M, Kl)
+        k = [gu.run_fwd(p, t["X"], t["W"], Y2)]
+        if act:
+            axo.axo_fc_dgrad_act(p, t["dY"].data_ptr(), Nl, t["W"].data_ptr(), Nl, t["pre"].data_ptr(), Kl, act,
+                                 dX2.data_ptr(), Kl, None, 0, gu.stream())
+        else:
+            k.append(gu.run_dgrad(p, t["dY"], t["W"], dX2))
+        torch.cuda.synchronize()
+        assert torch.equal(Y2, t["Y"]) and torch.equal(dX2, t["dX"])
+        if i == 1:
+            dW2 = torch.from_numpy(base32.copy()).to("cuda:0")
+            axo.axo_fc_wgrad_acc(p, t["X"].data_ptr(), Kl, t["dY"].data_ptr(), Nl, dW2.data_ptr(), Nl, None, 0, gu.stream())
+            torch.cuda.synchronize()
+            assert torch.equal(dW2, t["dW32"])
