@@ -210,10 +210,25 @@ struct SegCost {
     int count, item, small;
 };
 
+// A bias gradient inside a grouped launch (GroupItem::pair == PAIR_BIAS_GRAD, Mo = rows, No =
+// columns): strips of 64 columns, each a workgroup that streams Mo rows of 128 bytes.  A strip
+// is bound by memory latency, not bandwidth: measured 19 us for 4096 rows, which is what 15
+// reduction steps of a big tile take.
+constexpr int PAIR_BIAS_GRAD = 3;
+double bias_strip_cost(int rows) { return 1.0 + 15.0 * rows / 4096.0; }
+int bias_strips(int cols) { return (cols + axo::GROUP_BIAS_COLS - 1) / axo::GROUP_BIAS_COLS; }
+// The standalone launch picks its strip width by shape; only shapes for which it picks the
+// grouped launch's 64 columns may ride along, so that both give the same bits.
+bool bias_grad_groupable(const axo::BiasGradArgs& g) { return g.Nl > 0 && bias_strips(g.Nl) >= NUM_CU / 4; }
+
 // segments of a group for a choice of big_cols per item, most expensive tiles first
 std::vector<SegCost> group_segments(const std::vector<GroupItem>& items, const std::vector<int>& big_cols) {
     std::vector<SegCost> segs;
     for (size_t i = 0; i < items.size(); ++i) {
+        if (items[i].pair == PAIR_BIAS_GRAD) {
+            segs.push_back({bias_strip_cost(items[i].Mo), bias_strips(items[i].No), (int)i, 0});
+            continue;
+        }
         const int tiles_m = items[i].Mo / 256, cb = big_cols[i], cs = (items[i].No - cb * 256) / 128;
         if (cb > 0) segs.push_back({tile_cost(items[i].R, false), tiles_m * cb, (int)i, 0});
         if (cs > 0) segs.push_back({tile_cost(items[i].R, true), tiles_m * cs, (int)i, 1});
@@ -245,10 +260,11 @@ std::vector<int> plan_group(const std::vector<GroupItem>& items) {
     auto it = cache.find(items);
     if (it != cache.end()) return it->second;
     std::vector<int> cols(items.size());
-    for (size_t i = 0; i < items.size(); ++i) cols[i] = items[i].No / 256;
+    for (size_t i = 0; i < items.size(); ++i) cols[i] = items[i].pair == PAIR_BIAS_GRAD ? 0 : items[i].No / 256;
     double best = group_makespan(group_segments(items, cols));
     for (int sweep = 0; sweep < 2; ++sweep)
         for (size_t i = 0; i < items.size(); ++i) {
+            if (items[i].pair == PAIR_BIAS_GRAD) continue;
             const int max_cols = items[i].No / 256;
             const int stride = max_cols > 16 ? (max_cols + 15) / 16 : 1;
             int best_c = cols[i];
@@ -298,7 +314,9 @@ int launch_group(const Plan* const* plans, int n, hipStream_t st) {
     if (!raise_lds_limit(reinterpret_cast<const void*>(axo::gemm_group_kernel), &raised)) return AXO_ERR_HIP;
     std::vector<GroupItem> items(n);
     for (int i = 0; i < n; ++i)
-        items[i] = {plans[i]->g.Mo, plans[i]->g.No, plans[i]->g.R, layout_pair(plans[i]->la, plans[i]->lb)};
+        items[i] = plans[i]->bias_grad ? GroupItem{plans[i]->bg.M, plans[i]->bg.Nl, 0, PAIR_BIAS_GRAD}
+                                       : GroupItem{plans[i]->g.Mo, plans[i]->g.No, plans[i]->g.R,
+                                                   layout_pair(plans[i]->la, plans[i]->lb)};
     const std::vector<int> cols = plan_group(items);
     const std::vector<SegCost> segs = group_segments(items, cols);
     axo::GroupArgs ga{};
@@ -310,14 +328,35 @@ int launch_group(const Plan* const* plans, int n, hipStream_t st) {
         sg.first_block = blocks;
         sg.n_blocks = sc.count;
         sg.product = sc.item;
-        sg.kind = 2 * items[sc.item].pair + sc.small;
-        sg.tiles_m = items[sc.item].Mo / 256;
-        sg.cols = sc.count / sg.tiles_m;
-        sg.col0 = sc.small ? cols[sc.item] * 256 : 0;
-        sg.group_m = sg.tiles_m < 4 ? sg.tiles_m : 4;
+        if (items[sc.item].pair == PAIR_BIAS_GRAD) {
+            sg.kind = axo::GROUP_KIND_BIAS_GRAD;
+            sg.tiles_m = 1;
+            sg.cols = sc.count;
+            sg.col0 = 0;
+            sg.group_m = 1;
+        } else {
+            sg.kind = 2 * items[sc.item].pair + sc.small;
+            sg.tiles_m = items[sc.item].Mo / 256;
+            sg.cols = sc.count / sg.tiles_m;
+            sg.col0 = sc.small ? cols[sc.item] * 256 : 0;
+            sg.group_m = sg.tiles_m < 4 ? sg.tiles_m : 4;
+        }
         blocks += sc.count;
     }
-    for (int i = 0; i < n; ++i) ga.g[i] = plans[i]->g;
+    for (int i = 0; i < n; ++i) {
+        if (!plans[i]->bias_grad) {
+            ga.g[i] = plans[i]->g;
+            continue;
+        }
+        GemmArgs b{};  // the bias gradient's arguments in a GemmArgs, as gemm_group_kernel reads them
+        b.A = plans[i]->bg.dY;
+        b.lda = plans[i]->bg.lddy;
+        b.C = reinterpret_cast<axo::bf16_t*>(plans[i]->bg.db);
+        b.Mo = plans[i]->bg.M;
+        b.No = plans[i]->bg.Nl;
+        b.epilogue = plans[i]->bg.accumulate;
+        ga.g[i] = b;
+    }
     hipLaunchKernelGGL(axo::gemm_group_kernel, dim3(blocks), dim3(axo::TILE_THREADS), axo::MIX_LDS_BYTES, st, ga);
     return hipGetLastError() == hipSuccess ? AXO_OK : AXO_ERR_HIP;
 }
@@ -610,19 +649,31 @@ int dependence_levels(const std::vector<Plan>& plans, std::vector<int>* level) {
 // grouped launches (GROUP_MAX_PRODUCTS per launch), the others get a launch of their own.
 int enqueue_by_level(const std::vector<Plan>& plans, const std::vector<int>& level, int levels, hipStream_t st) {
     int rc = AXO_OK;
-    std::vector<const Plan*> group;
+    std::vector<const Plan*> group;   // products of the level the tiled kernel takes
+    std::vector<const Plan*> riders;  // bias gradients of the level that may share their launch
     auto flush = [&]() {
         if (group.empty() || rc != AXO_OK) return;
         rc = group.size() == 1 ? launch_tile_layout(group[0]->g, group[0]->la, group[0]->lb, st)
                                : launch_group(group.data(), (int)group.size(), st);
         group.clear();
     };
+    // the last launch of a level takes the level's bias gradients along, as many as fit
+    auto flush_level = [&]() {
+        while (!riders.empty() && !group.empty() && (int)group.size() < axo::GROUP_MAX_PRODUCTS) {
+            group.push_back(riders.back());
+            riders.pop_back();
+        }
+        flush();
+        for (size_t k = 0; k < riders.size() && rc == AXO_OK; ++k) rc = launch_bias_grad(riders[k]->bg, st);
+        riders.clear();
+    };
     for (int lv = 0; lv < levels && rc == AXO_OK; ++lv) {
         for (size_t i = 0; i < plans.size() && rc == AXO_OK; ++i) {
             const Plan& pl = plans[i];
             if (level[i] != lv || pl.nothing_to_do()) continue;
             if (pl.bias_grad) {
-                rc = launch_bias_grad(pl.bg, st);
+                if (bias_grad_groupable(pl.bg)) riders.push_back(&pl);
+                else rc = launch_bias_grad(pl.bg, st);
                 continue;
             }
             if (!tileable(pl.g, pl.la, pl.lb)) {
@@ -632,7 +683,7 @@ int enqueue_by_level(const std::vector<Plan>& plans, const std::vector<int>& lev
             group.push_back(&pl);
             if ((int)group.size() == axo::GROUP_MAX_PRODUCTS) flush();
         }
-        flush();
+        flush_level();
     }
     return rc;
 }

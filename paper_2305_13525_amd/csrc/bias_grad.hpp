@@ -25,30 +25,47 @@ struct BiasGradArgs {
     int accumulate;  // 0: db = sums, 1: db += sums
 };
 
-template <int COLS>
-__global__ void __launch_bounds__(BG_THREADS) bias_grad_kernel(BiasGradArgs g) {
-    constexpr int CX = COLS / 8, ROWS = BG_THREADS / CX;
-    __shared__ float part[ROWS][COLS + 1];
+// One strip of COLS columns, summed by a workgroup of THREADS threads (1024, or 512 inside the
+// grouped GEMM launch); part: ROWS128 x (COLS + 1) floats of LDS.  The reduction has the shape of
+// the 1024-thread one whatever THREADS is: 128 row lanes (1024 / 8 column lanes at COLS = 64), each
+// summing rows t = r, r + 128, ..., then a binary tree over the row lanes; with 512 threads every
+// thread plays row lanes r and r + 64 and adds the two sums itself, which is the tree's first
+// level.  So both forms give the same bits.
+template <int COLS, int THREADS>
+__device__ __forceinline__ void bias_grad_strip(const BiasGradArgs& g, int strip, float* part_lds) {
+    constexpr int CX = COLS / 8, LANES = BG_THREADS / CX;  // row lanes of the reference shape
+    constexpr int ROWS = THREADS / CX;                     // row lanes this workgroup really has
+    constexpr int FOLD = LANES / ROWS;                     // reference lanes per thread (1 or 2)
+    static_assert(FOLD == 1 || FOLD == 2, "1024 or 512 threads");
+    float(*part)[COLS + 1] = reinterpret_cast<float(*)[COLS + 1]>(part_lds);
     const int cx = threadIdx.x % CX, ry = threadIdx.x / CX;
-    const int col = blockIdx.x * COLS + cx * 8;
+    const int col = strip * COLS + cx * 8;
     const int valid = g.Nl - col;  // columns of this thread's chunk inside the matrix (may be <= 0 or >= 8)
-    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (valid >= 8) {
-#pragma unroll 4
-        for (int t = ry; t < g.M; t += ROWS) {
-            const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(g.dY + (int64_t)t * g.lddy + col));
+    float s[FOLD][8];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                s[2 * i] += __uint_as_float(w[i] << 16);
-                s[2 * i + 1] += __uint_as_float(w[i] & 0xFFFF0000u);
+    for (int f = 0; f < FOLD; ++f)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s[f][i] = 0.f;
+#pragma unroll
+    for (int f = 0; f < FOLD; ++f) {
+        const int r0 = ry + f * ROWS;
+        if (valid >= 8) {
+#pragma unroll 4
+            for (int t = r0; t < g.M; t += LANES) {
+                const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(g.dY + (int64_t)t * g.lddy + col));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    s[f][2 * i] += __uint_as_float(w[i] << 16);
+                    s[f][2 * i + 1] += __uint_as_float(w[i] & 0xFFFF0000u);
+                }
             }
+        } else if (valid > 0) {  // ragged last chunk
+            for (int t = r0; t < g.M; t += LANES)
+                for (int i = 0; i < valid; ++i) s[f][i] += bf16_bits_to_f32(g.dY[(int64_t)t * g.lddy + col + i]);
         }
-    } else if (valid > 0) {  // ragged last chunk
-        for (int t = ry; t < g.M; t += ROWS)
-            for (int i = 0; i < valid; ++i) s[i] += bf16_bits_to_f32(g.dY[(int64_t)t * g.lddy + col + i]);
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) part[ry][cx * 8 + i] = s[i];
+    for (int i = 0; i < 8; ++i) part[ry][cx * 8 + i] = FOLD == 2 ? s[0][i] + s[FOLD - 1][i] : s[0][i];
     __syncthreads();
     for (int half = ROWS / 2; half >= 1; half >>= 1) {  // fixed-shape tree over the row lanes
         if (ry < half) {
@@ -65,6 +82,12 @@ __global__ void __launch_bounds__(BG_THREADS) bias_grad_kernel(BiasGradArgs g) {
                 g.db[col + i] = g.accumulate ? g.db[col + i] + v : v;
             }
     }
+}
+
+template <int COLS>
+__global__ void __launch_bounds__(BG_THREADS) bias_grad_kernel(BiasGradArgs g) {
+    __shared__ float part[(BG_THREADS / (COLS / 8)) * (COLS + 1)];
+    bias_grad_strip<COLS, BG_THREADS>(g, blockIdx.x, part);
 }
 
 }  // namespace axo

@@ -37,6 +37,7 @@
 #include <type_traits>
 
 #include "axo_common.hpp"
+#include "bias_grad.hpp"
 
 namespace axo {
 
@@ -548,12 +549,16 @@ struct GroupSeg {
     int first_block;  // first workgroup id of the segment
     int n_blocks;
     int product;      // index into GroupArgs::g
-    int kind;         // 2 * layout pair (0: KC/MC, 1: KC/KC, 2: MC/MC) + (1 if 256x128 tiles)
+    int kind;         // 2 * layout pair (0: KC/MC, 1: KC/KC, 2: MC/MC) + (1 if 256x128 tiles);
+                      // GROUP_KIND_BIAS_GRAD: 64-column strips of a bias gradient
     int tiles_m;      // tile rows
     int cols;         // tile columns of this segment
     int col0;         // first output column of this segment
     int group_m;      // band height of the tile order
 };
+
+constexpr int GROUP_KIND_BIAS_GRAD = 6;
+constexpr int GROUP_BIAS_COLS = 64;
 
 struct GroupArgs {
     int n_seg;
@@ -569,6 +574,20 @@ __global__ void __launch_bounds__(TILE_THREADS, 1) gemm_group_kernel(GroupArgs g
         if (bid >= ga.seg[i].first_block) si = i;
     const GroupSeg sg = ga.seg[si];
     const GemmArgs g = ga.g[sg.product];
+    if (sg.kind == GROUP_KIND_BIAS_GRAD) {
+        // A bias gradient rides along: memory-bound strips that fill CUs the products leave idle
+        // towards the end of the launch.  Its arguments travel in a GemmArgs: A = dY, C = db (fp32),
+        // Mo = rows, No = columns, epilogue = accumulate flag.
+        BiasGradArgs bg;
+        bg.dY = g.A;
+        bg.lddy = g.lda;
+        bg.db = reinterpret_cast<float*>(g.C);
+        bg.M = g.Mo;
+        bg.Nl = g.No;
+        bg.accumulate = g.epilogue;
+        bias_grad_strip<GROUP_BIAS_COLS, TILE_THREADS>(bg, bid - sg.first_block, reinterpret_cast<float*>(smem));
+        return;
+    }
     int tm, tn;
     // workgroup ids with equal id % 8 share an XCD whatever the segment's first id is
     tile_of_index(xcd_contiguous(bid - sg.first_block, sg.n_blocks), sg.tiles_m, sg.cols, sg.group_m, tm, tn);

@@ -117,12 +117,14 @@ def test_bias_grad_in_place_columns():
 
 
 def test_layer_step_ext_against_single_calls_and_oracle():
-    """axo_layer_step_ext on three layers with buffers of their own: a plain layer, one with all
-    three extras (dgrad through the tanh GELU, fp32 weight-gradient accumulation, bias gradient) and
-    one with the erf GELU and an accumulating bias gradient.  The chain is one dependence level, so
-    the fused products share a grouped launch with the plain ones.  Every output is checked against
-    the oracle, and bit for bit against the single calls."""
-    shapes = [(512, 256, 384), (768, 256, 640), (256, 384, 256)]
+    """axo_layer_step_ext on four layers with buffers of their own: a plain layer, one with all
+    three extras (dgrad through the tanh GELU, fp32 weight-gradient accumulation, bias gradient),
+    one with the erf GELU and an accumulating bias gradient, and a wide one (4608 columns, a row
+    count that is no multiple of the reduction's lane count) whose bias gradient is wide enough to
+    ride along in the grouped launch.  The chain is one dependence level, so the fused products
+    share a grouped launch with the plain ones.  Every output is checked against the oracle, and
+    bit for bit against the single calls."""
+    shapes = [(512, 256, 384), (768, 256, 640), (256, 384, 256), (520, 256, 4608)]
     rng = np.random.default_rng(31)
     keep, layers = [], []
     for i, (M, Kl, Nl) in enumerate(shapes):
@@ -141,9 +143,11 @@ def test_layer_step_ext_against_single_calls_and_oracle():
         elif i == 1:
             E = axo.LayerExt.make(L, pre=t["pre"].data_ptr(), ldpre=Kl, act_below=axo.AXO_EPI_BIAS_GELU_TANH,
                                   dW32=t["dW32"].data_ptr(), lddw32=Nl, db=t["db"].data_ptr(), accumulate_db=0)
-        else:
+        elif i == 2:
             E = axo.LayerExt.make(L, pre=t["pre"].data_ptr(), ldpre=Kl, act_below=axo.AXO_EPI_BIAS_GELU_ERF,
                                   db=t["db"].data_ptr(), accumulate_db=1)
+        else:
+            E = axo.LayerExt.make(L, db=t["db"].data_ptr(), accumulate_db=0)
         layers.append(E)
         keep.append((Xb, Wb, dYb, Pb, base32, basedb, t))
     axo.axo_layer_step_ext(layers, None, 0, gu.stream())
@@ -167,10 +171,15 @@ def test_layer_step_ext_against_single_calls_and_oracle():
         got_db = t["db"].cpu().numpy().astype(np.float64)
         if i == 0:
             assert np.array_equal(t["db"].cpu().numpy(), basedb)
-        elif i == 1:
+        elif i in (1, 3):
             assert np.max(np.abs(got_db - ref_db)) <= tol
         else:
             assert np.max(np.abs(got_db - (basedb.astype(np.float64) + ref_db))) <= tol
+        if i > 0:    # the stand-alone bias gradient sums in the same order: same bits
+            db2 = torch.from_numpy(basedb.copy()).to("cuda:0")
+            axo.axo_bias_grad(p, t["dY"].data_ptr(), Nl, db2.data_ptr(), 1 if i == 2 else 0, gu.stream())
+            torch.cuda.synchronize()
+            assert torch.equal(db2, t["db"])
         # the single calls give the same bits
         Y2, dX2 = gu.empty_dev(M, Nl), gu.empty_dev(M, Kl)
         k = [gu.run_fwd(p, t["X"], t["W"], Y2)]
