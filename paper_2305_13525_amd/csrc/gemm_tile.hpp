@@ -541,7 +541,9 @@ __global__ void __launch_bounds__(TILE_THREADS, 1) gemm_mixed_kernel(GemmArgs g,
 // chain of such launches pays a ramp-up and a tail each.  A group launch strings the tile lists of
 // up to GROUP_MAX_PRODUCTS products together: the grid is cut into segments, a segment is all the
 // tiles of one size of one product, and segments are ordered by decreasing tile cost so that the
-// in-order workgroup dispatch approximates longest-processing-time-first scheduling.
+// in-order workgroup dispatch approximates longest-processing-time-first scheduling.  One of the
+// slots may instead hold a bias gradient, whose 64-column strips form one more (cheap, hence
+// late) segment of memory-bound workgroups.
 constexpr int GROUP_MAX_PRODUCTS = 12;
 constexpr int GROUP_MAX_SEGMENTS = 2 * GROUP_MAX_PRODUCTS;
 
