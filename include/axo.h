@@ -247,8 +247,10 @@ typedef struct axo_layer_ext {
  * layers n-1..0 dgrad, wgrad, bias gradient.  Scheduling is that of axo_layer_step: dependence
  * levels from the byte ranges read and written (an accumulating call reads what it writes),
  * independent products of a level in grouped launches (the fused variants take part in them: they
- * differ from the plain products only in their epilogue), bias gradients as launches of their
- * own within their level.  Results are bit-identical to the single calls in program order.
+ * differ from the plain products only in their epilogue).  A bias gradient of at least 4033
+ * columns (the width from which the stand-alone call uses 64-column strips) rides along in its
+ * level's last grouped launch as a segment of memory-bound workgroups; narrower ones are launches
+ * of their own within their level.  Results are bit-identical to the single calls in program order.
  * Errors: those of the single calls; BAD_EPILOGUE (act_below not a GELU kind with pre != NULL, or
  * not 0 with pre == NULL); BAD_ARG (accumulate_db not 0/1, a reserved field not 0, n_layers < 0 or
  * > 4096).  On a validation error nothing is enqueued. */
