@@ -300,3 +300,52 @@ def test_layer_step_ext_validation():
     assert step([ext(nothing, dW32=A, lddw32=8)]) == OK                      # ... the fp32 one does not
     assert axo.library().axo_layer_step_ext(None, 1, None, 0, None) == NULL_PTR
     assert axo.library().axo_layer_step_ext(None, -1, None, 0, None) == BAD_ARG
+
+
+def test_dependence_levels_on_random_chains():
+    """Property check of axo_layer_step_levels on seeded random chains whose buffers are drawn from
+    a small pool (so that reads and writes collide often).  The byte ranges and the conflict rule
+    are restated here in Python; the library's levels must (i) put every product above all earlier
+    products it conflicts with and (ii) be minimal: each product sits exactly one above the
+    highest conflicting earlier product, or at 0."""
+    import random
+    M, K, N = 64, 32, 48
+    p = axo.Problem.make((1, 1, 1), (0, 0, 0), M, K, N)
+    base, slot = 1 << 22, 1 << 15            # slots are larger than any matrix here (at most 64 * 48 * 2 bytes)
+    span = lambda rows, cols, ld: ((rows - 1) * ld + cols) * 2
+
+    def products(lay):
+        X, W, Y, dY, dX, dW = lay
+        rng = lambda ptr, rows, cols, ld: (ptr, ptr + span(rows, cols, ld))
+        fwd = ([rng(X, M, K, K), rng(W, K, N, N)], rng(Y, M, N, N))
+        dg = ([rng(dY, M, N, N), rng(W, K, N, N)], rng(dX, M, K, K))
+        wg = ([rng(X, M, K, K), rng(dY, M, N, N)], rng(dW, K, N, N))
+        return fwd, dg, wg
+
+    def conflict(a, b):      # a earlier than b
+        ov = lambda r, q: r[0] < q[1] and q[0] < r[1]
+        return ov(a[1], b[1]) or any(ov(a[1], r) for r in b[0]) or any(ov(r, b[1]) for r in a[0])
+
+    rnd = random.Random(7)
+    for case in range(150):
+        n = rnd.randint(1, 6)
+        pool = [base + i * slot for i in range(rnd.randint(6, 6 * n + 2))]
+        # half-slot offsets make partial overlaps as well as exact aliases
+        pick = lambda: rnd.choice(pool) + rnd.choice((0, 0, 0, 1 << 11))
+        lays = []
+        for _ in range(n):
+            X, W, Y, dY, dX, dW = (pick() for _ in range(6))
+            lays.append((X, W, Y, dY, dX, dW))
+        layers = [axo.Layer(p, 0, 0, X, K, W, N, None, Y, N, dY, N, dX, K, dW, N) for X, W, Y, dY, dX, dW in lays]
+        rc, n_levels, lv = axo.axo_layer_step_levels(layers)
+        assert rc == OK and len(lv) == 3 * n
+        prods = [products(l)[0] for l in lays]                       # program order: forwards ...
+        for l in reversed(lays):                                      # ... then dgrad, wgrad of layers n-1..0
+            prods += list(products(l)[1:])
+        for j in range(3 * n):
+            want = 0
+            for i in range(j):
+                if conflict(prods[i], prods[j]):
+                    want = max(want, lv[i] + 1)
+            assert lv[j] == want, (case, j, lv)
+        assert n_levels == max(lv) + 1
