@@ -443,3 +443,42 @@ def test_denormals_infinities_and_nans():
     assert inf_cols.sum() == Nl - 1
     assert np.array_equal(np.isinf(gotf[2]), inf_cols) and np.array_equal(np.sign(gotf[2][inf_cols]), np.sign(ref[2][inf_cols]))
     assert np.isnan(ref[3]).all() and np.isnan(gotf[3]).all()
+
+
+def test_scheduled_step_equals_ordered_step_on_random_dependent_chains():
+    """Seeded random chains whose buffers are drawn from a small pool of equally shaped matrices, so
+    that products read what others write, overwrite what others read and write to the same place
+    in many combinations.  axo_layer_step (dependence levels, grouped launches) must leave every
+    buffer of the pool exactly as axo_layer_step_ordered (one launch per product, program order)
+    does.  A dependence the analysis missed would let two products race and show up here."""
+    import random
+    D = 256                                    # M = Kl = Nl: every buffer can play every role
+    p = P(D, D, D)
+    rnd = random.Random(11)
+    sigma = 1.0 / 16.0                         # keeps magnitudes stable through chained products
+    n_levels_seen = set()
+    for case in range(12):
+        n = rnd.randint(2, 4)
+        pool_bits = [syn.normal_bf16(1000 + case, k, (D, D), sigma) for k in range(rnd.randint(5, 4 * n))]
+        choose = lambda banned=(): rnd.choice([i for i in range(len(pool_bits)) if i not in banned])
+        roles = []
+        for _ in range(n):
+            X, W, dY = choose(), choose(), choose()
+            Y = choose((X, W))                 # a product's output may not overlap its own inputs
+            dX = choose((dY, W))
+            dW = choose((X, dY))
+            roles.append((X, W, Y, dY, dX, dW))
+        results = []
+        for step in (axo.axo_layer_step, axo.axo_layer_step_ordered):
+            pool = [gu.to_dev(b) for b in pool_bits]
+            layers = [axo.Layer(p, 0, 0, pool[X].data_ptr(), D, pool[W].data_ptr(), D, None, pool[Y].data_ptr(), D,
+                                pool[dY].data_ptr(), D, pool[dX].data_ptr(), D, pool[dW].data_ptr(), D)
+                      for X, W, Y, dY, dX, dW in roles]
+            if step is axo.axo_layer_step:
+                n_levels_seen.add(axo.axo_layer_step_levels(layers)[1])
+            step(layers, None, 0, gu.stream())
+            torch.cuda.synchronize()
+            results.append(pool)
+        for k, (a, b) in enumerate(zip(*results)):
+            assert torch.equal(a, b), (case, k, roles)
+    assert len(n_levels_seen) >= 3             # the cases really differ in their dependence structure
