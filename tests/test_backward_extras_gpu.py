@@ -13,7 +13,8 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 import gpu_util as gu  # noqa: E402
 
-SHAPES = [(256, 256, 256), (512, 384, 640), (300, 72, 136), (1024, 128, 1280), (77, 40, 24), (768, 256, 1152)]
+SHAPES = [(256, 256, 256), (512, 384, 640), (300, 72, 136), (1024, 128, 1280), (77, 40, 24), (768, 256, 1152),
+          (520, 264, 384), (384, 264, 136)]   # the last two: tuned interior plus general-kernel strips
 
 
 def P(M, Kl, Nl):
