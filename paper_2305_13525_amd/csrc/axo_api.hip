@@ -8,6 +8,7 @@
 #include <algorithm>
 #include <atomic>
 #include <cstdlib>
+#include <deque>
 #include <functional>
 #include <map>
 #include <mutex>
@@ -282,48 +283,6 @@ std::vector<int> plan_group(const std::vector<GroupItem>& items) {
     return cols;
 }
 
-// The product restricted to output rows [r0, r0 + rows) and columns [c0, c0 + cols): the same
-// operands and output addressed through offset pointers, same leading dimensions.  The offsets
-// used below keep the 16-byte alignment the kernels load and store with: row offsets always do
-// (leading dimensions are multiples of 8 elements, or of 4 floats), r0 is a multiple of 256 and
-// c0 a multiple of 128.
-GemmArgs sub_product(const GemmArgs& g, int la, int lb, int r0, int rows, int c0, int cols) {
-    GemmArgs s = g;
-    s.A = la == axo::KC ? g.A + (int64_t)r0 * g.lda : g.A + r0;   // KC: row i of A; MC: column i of A
-    s.B = lb == axo::KC ? g.B + (int64_t)c0 * g.ldb : g.B + c0;
-    if (g.epilogue == axo::EPI_ACC_F32)                           // C counts fp32 elements
-        s.C = reinterpret_cast<axo::bf16_t*>(reinterpret_cast<float*>(g.C) + (int64_t)r0 * g.ldc + c0);
-    else
-        s.C = g.C + (int64_t)r0 * g.ldc + c0;
-    if (g.bias) s.bias = g.bias + c0;
-    if (g.aux) s.aux = g.aux + (int64_t)r0 * g.ldaux + c0;
-    s.Mo = rows;
-    s.No = cols;
-    return s;
-}
-
-// One product: the tuned kernel when it takes the shape, the general kernel otherwise.  A shape
-// that only misses the tuned kernel's output granularity (256 rows, 128 columns) is cut in three:
-// the interior of whole tiles goes to the tuned kernel, the strip of leftover columns (all rows)
-// and the strip of leftover rows (interior columns) to the general kernel.  The three write
-// disjoint parts of the output and follow each other on the stream.  (Measured on
-// 4096 x 2048 x 6152, eight columns over: 198 TFLOP/s through the general kernel alone.)
-int launch(const GemmArgs& g, int la, int lb, hipStream_t st) {
-    if (g.Mo == 0 || g.No == 0) return AXO_OK;
-    if (tileable(g, la, lb)) return launch_tile_layout(g, la, lb, st);
-    const int Mi = g.Mo / 256 * 256, Ni = g.No / 128 * 128;
-    if (Mi > 0 && Ni > 0) {
-        const GemmArgs interior = sub_product(g, la, lb, 0, Mi, 0, Ni);
-        if (tileable(interior, la, lb)) {
-            int rc = launch_tile_layout(interior, la, lb, st);
-            if (rc == AXO_OK && g.No > Ni) rc = launch_generic(sub_product(g, la, lb, 0, g.Mo, Ni, g.No - Ni), la, lb, st);
-            if (rc == AXO_OK && g.Mo > Mi) rc = launch_generic(sub_product(g, la, lb, Mi, g.Mo - Mi, 0, Ni), la, lb, st);
-            return rc;
-        }
-    }
-    return launch_generic(g, la, lb, st);
-}
-
 int check_workspace(const axo_problem_t* p, int op, const void* ws, size_t ws_bytes) {
     const size_t need = axo_workspace_bytes(p, op);
     if (need == 0) return AXO_OK;
@@ -394,6 +353,81 @@ int launch_group(const Plan* const* plans, int n, hipStream_t st) {
     }
     hipLaunchKernelGGL(axo::gemm_group_kernel, dim3(blocks), dim3(axo::TILE_THREADS), axo::MIX_LDS_BYTES, st, ga);
     return hipGetLastError() == hipSuccess ? AXO_OK : AXO_ERR_HIP;
+}
+
+// The product restricted to output rows [r0, r0 + rows) and columns [c0, c0 + cols): the same
+// operands and output addressed through offset pointers, same leading dimensions.
+GemmArgs sub_product(const GemmArgs& g, int la, int lb, int r0, int rows, int c0, int cols) {
+    GemmArgs s = g;
+    s.A = la == axo::KC ? g.A + (int64_t)r0 * g.lda : g.A + r0;   // KC: row i of A; MC: column i of A
+    s.B = lb == axo::KC ? g.B + (int64_t)c0 * g.ldb : g.B + c0;
+    if (g.epilogue == axo::EPI_ACC_F32)                           // C counts fp32 elements
+        s.C = reinterpret_cast<axo::bf16_t*>(reinterpret_cast<float*>(g.C) + (int64_t)r0 * g.ldc + c0);
+    else
+        s.C = g.C + (int64_t)r0 * g.ldc + c0;
+    if (g.bias) s.bias = g.bias + c0;
+    if (g.aux) s.aux = g.aux + (int64_t)r0 * g.ldaux + c0;
+    s.Mo = rows;
+    s.No = cols;
+    return s;
+}
+
+// A product whose reduction fits the tuned kernel but whose output misses its granularity (256
+// rows, 128 columns) can still be covered with whole tiles: the interior, plus a band of the last
+// 256 rows and a band of the last 128 columns that reach back over the interior.  Where bands and
+// interior overlap an element is computed twice, by the same instructions in the same order (its
+// value does not depend on the tile it falls in), so the second store rewrites the same bits.
+// Conditions: the shifted origins must keep the 16-byte alignment of the loads and stores, i.e.
+// No % 8 == 0 and, where the output row index is the contiguous one of operand A (wgrad),
+// Mo % 8 == 0; and the epilogue must be a pure function of the sum (not the fp32 accumulation,
+// which would add twice).  On success `out` receives 2 to 4 tileable pieces.
+bool cover_with_tiles(const Plan& pl, std::vector<Plan>* out) {
+    const GemmArgs& g = pl.g;
+    if (g.epilogue == axo::EPI_ACC_F32 || g.Mo < 256 || g.No < 128 || g.No % 8 != 0) return false;
+    if (pl.la == axo::MC && g.Mo % 8 != 0) return false;
+    const int Mi = g.Mo / 256 * 256, Ni = g.No / 128 * 128;
+    int rows[2][2] = {{0, Mi}, {g.Mo - 256, 256}}, cols[2][2] = {{0, Ni}, {g.No - 128, 128}};
+    const int nr = g.Mo > Mi ? 2 : 1, nc = g.No > Ni ? 2 : 1;
+    out->clear();
+    for (int a = 0; a < nr; ++a)
+        for (int b = 0; b < nc; ++b) {
+            Plan piece = pl;
+            piece.g = sub_product(g, pl.la, pl.lb, rows[a][0], rows[a][1], cols[b][0], cols[b][1]);
+            if (!tileable(piece.g, pl.la, pl.lb)) return false;
+            out->push_back(piece);
+        }
+    return out->size() > 1;
+}
+
+// One product: the tuned kernel when it takes the shape; a cover of whole tiles in one grouped
+// launch when only the output's granularity is in the way (measured on 4096 x 2048 x 6152, eight
+// columns over: 198 TFLOP/s through the general kernel alone); failing that, the interior on the
+// tuned kernel and the leftover strips on the general one; the general kernel for the rest.
+int launch(const GemmArgs& g, int la, int lb, hipStream_t st) {
+    if (g.Mo == 0 || g.No == 0) return AXO_OK;
+    if (tileable(g, la, lb)) return launch_tile_layout(g, la, lb, st);
+    Plan whole;
+    whole.g = g;
+    whole.la = la;
+    whole.lb = lb;
+    std::vector<Plan> pieces;
+    if (cover_with_tiles(whole, &pieces)) {
+        const Plan* ptr[4];
+        for (size_t i = 0; i < pieces.size(); ++i) ptr[i] = &pieces[i];
+        return launch_group(ptr, (int)pieces.size(), st);
+    }
+    const int Mi = g.Mo / 256 * 256, Ni = g.No / 128 * 128;
+    if (Mi > 0 && Ni > 0) {
+        const GemmArgs interior = sub_product(g, la, lb, 0, Mi, 0, Ni);
+        // block offsets that are multiples of 256 rows and 128 columns keep every alignment
+        if (tileable(interior, la, lb)) {
+            int rc = launch_tile_layout(interior, la, lb, st);
+            if (rc == AXO_OK && g.No > Ni) rc = launch_generic(sub_product(g, la, lb, 0, g.Mo, Ni, g.No - Ni), la, lb, st);
+            if (rc == AXO_OK && g.Mo > Mi) rc = launch_generic(sub_product(g, la, lb, Mi, g.Mo - Mi, 0, Ni), la, lb, st);
+            return rc;
+        }
+    }
+    return launch_generic(g, la, lb, st);
 }
 
 int plan_fwd(const axo_problem_t* p, const void* X, int64_t ldx, const void* W, int64_t ldw, const void* bias,
@@ -684,6 +718,7 @@ int dependence_levels(const std::vector<Plan>& plans, std::vector<int>* level) {
 // grouped launches (GROUP_MAX_PRODUCTS per launch), the others get a launch of their own.
 int enqueue_by_level(const std::vector<Plan>& plans, const std::vector<int>& level, int levels, hipStream_t st) {
     int rc = AXO_OK;
+    std::deque<Plan> covers;          // pieces of covered products (a deque keeps their addresses)
     std::vector<const Plan*> group;   // products of the level the tiled kernel takes
     std::vector<const Plan*> riders;  // bias gradients of the level that may share their launch
     auto flush = [&]() {
@@ -712,7 +747,17 @@ int enqueue_by_level(const std::vector<Plan>& plans, const std::vector<int>& lev
                 continue;
             }
             if (!tileable(pl.g, pl.la, pl.lb)) {
-                rc = launch(pl.g, pl.la, pl.lb, st);
+                std::vector<Plan> pieces;
+                if (!cover_with_tiles(pl, &pieces)) {
+                    rc = launch(pl.g, pl.la, pl.lb, st);
+                    continue;
+                }
+                if (group.size() + pieces.size() > (size_t)axo::GROUP_MAX_PRODUCTS) flush();
+                for (const Plan& piece : pieces) {  // the pieces of a cover share the level's grouped launch
+                    covers.push_back(piece);
+                    group.push_back(&covers.back());
+                }
+                if ((int)group.size() >= axo::GROUP_MAX_PRODUCTS) flush();
                 continue;
             }
             group.push_back(&pl);
