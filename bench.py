@@ -97,15 +97,24 @@ def main() -> int:
         for _ in range(warmup):
             step_fn(objs, wsp, nws, st)
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        # one event per eighth of the run as well (no synchronisation inside the timed region): the
+        # spread between the chunks shows clock drift that the mean hides
+        chunk = max(1, steps // 8)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps // chunk + 1)]
         t0 = time.perf_counter()
-        e0.record()
-        for _ in range(steps):
+        marks[0].record()
+        for i in range(steps):
             step_fn(objs, wsp, nws, st)
+            if (i + 1) % chunk == 0:
+                marks[(i + 1) // chunk].record()
+        e1 = torch.cuda.Event(enable_timing=True)
         e1.record()
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3
-        return max(e0.elapsed_time(e1), 0.0) / steps, wall / steps
+        per_chunk = sorted(marks[k].elapsed_time(marks[k + 1]) / chunk for k in range(steps // chunk))
+        time_step.chunks = {"steps_per_chunk": chunk, "median_ms": round(per_chunk[len(per_chunk) // 2], 5),
+                            "best_ms": round(per_chunk[0], 5), "worst_ms": round(per_chunk[-1], 5)}
+        return max(marks[0].elapsed_time(e1), 0.0) / steps, wall / steps
 
     def time_op(fn, steps, warmup):
         for _ in range(warmup):
@@ -140,6 +149,7 @@ def main() -> int:
 
     layers, objs, keep, flop, wsp, nws = setup(args.config)
     ms, wall_ms = time_step(objs, wsp, nws, args.steps, args.warmup)
+    chunk_stats = dict(time_step.chunks)
     tflops = flop / (ms * 1e-3) / 1e12
 
     # per-product launches of the largest layer, each timed in a loop of its own
@@ -171,7 +181,8 @@ def main() -> int:
 
     out = {"metric": "TFLOP/s for fwd+dgrad+wgrad shard GEMMs, 1 MI355X", "value": round(tflops, 2),
            "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-           "ms_per_step": round(ms, 5), "wall_ms_per_step": round(wall_ms, 5), "higher_is_better": True,
+           "ms_per_step": round(ms, 5), "wall_ms_per_step": round(wall_ms, 5), "ms_per_step_chunks": chunk_stats,
+           "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
            "config": {"workload": args.config,
