@@ -95,9 +95,13 @@ bool span_ok(int layout, int64_t ld, int R) {
     return elems * 2 < (int64_t)0xFFFF0000;
 }
 
+// Reductions: multiples of 128 (the loop is unrolled over two 64-wide LDS stages), except where
+// both operands have the reduction index as their row index (wgrad): there the kernel rounds the
+// length up itself and reads the surplus rows as zeros, so any length goes.
 bool tileable(const GemmArgs& g, int la, int lb) {
-    return g.R > 0 && g.R % (2 * axo::TILE_BK) == 0 && g.Mo > 0 && g.No > 0 && g.Mo % 256 == 0 && g.No % 128 == 0 &&
-           span_ok(la, g.lda, g.R) && span_ok(lb, g.ldb, g.R);
+    const bool any_reduction = la == axo::MC && lb == axo::MC;
+    return g.R > 0 && (any_reduction || g.R % (2 * axo::TILE_BK) == 0) && g.Mo > 0 && g.No > 0 && g.Mo % 256 == 0 &&
+           g.No % 128 == 0 && span_ok(la, g.lda, g.R) && span_ok(lb, g.ldb, g.R);
 }
 
 // Time (in big-tile units) a greedy dispatch of n_big big tiles followed by n_small small tiles

@@ -241,23 +241,37 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
-    const int KT = g.R / TILE_BK;
+    // Both operands of wgrad have the reduction index as their row index (MC).  Rows at or beyond
+    // the end of the reduction can then be made to read as zeros by the buffer descriptor's range
+    // check, so that instantiation takes ANY reduction length: it walks the length rounded up to
+    // the next multiple of 128 and the surplus rows contribute nothing.  (A KC operand has the
+    // reduction inside its rows; its overrun lands in the next row, which no linear bound can mask,
+    // so the other products keep to multiples of 128.)
+    constexpr bool CLAMPED = (LA == MC && LB == MC);
+    const int KT = CLAMPED ? (g.R + 2 * TILE_BK - 1) / (2 * TILE_BK) * 2 : g.R / TILE_BK;
 
     // global side: descriptor at the tile origin, per-lane offsets, scalar step
     const bf16_t* Ab = (LA == KC) ? g.A + (int64_t)i0 * g.lda : g.A + i0;
     const bf16_t* Bb = (LB == KC) ? g.B + (int64_t)j0 * g.ldb : g.B + j0;
-    // raw buffer descriptor: base, stride 0, no bound (the host checked the spans), dword format
-    auto make_rsrc = [](const bf16_t* p) __attribute__((always_inline)) {
+    // raw buffer descriptor: base, stride 0, dword format.  Bound: none for KC operands (the host
+    // checked the spans).  For the clamped instantiation the bound is the number of bytes from the
+    // tile origin to the end of the tile's columns in the last row of the reduction.  On this
+    // chip the range check covers the sum of the per-lane offset and the scalar offset that
+    // carries the reduction step (measured: lowering the bound by the scalar offset at every step
+    // zeroed the second half of the reduction), so one constant bound serves the whole walk.
+    auto make_rsrc = [](const bf16_t* p, uint32_t bound) __attribute__((always_inline)) {
         const uint64_t v = reinterpret_cast<uint64_t>(p);
         u32x4_t r;
         r[0] = __builtin_amdgcn_readfirstlane((uint32_t)v);
         r[1] = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32) & 0xFFFFu);
-        r[2] = 0xFFFFFFFFu;
+        r[2] = __builtin_amdgcn_readfirstlane(bound);
         r[3] = 0x00020000u;
         return r;
     };
-    const u32x4_t a_rsrc = make_rsrc(Ab);
-    const u32x4_t b_rsrc = make_rsrc(Bb);
+    const uint32_t a_valid = CLAMPED ? (uint32_t)((((int64_t)g.R - 1) * g.lda + BM) * 2) : 0xFFFFFFFFu;
+    const uint32_t b_valid = CLAMPED ? (uint32_t)((((int64_t)g.R - 1) * g.ldb + BN) * 2) : 0xFFFFFFFFu;
+    const u32x4_t a_rsrc = make_rsrc(Ab, a_valid);
+    const u32x4_t b_rsrc = make_rsrc(Bb, b_valid);
     const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
     const uint32_t a_step = (uint32_t)((LA == KC) ? TILE_BK * 2 : (int64_t)TILE_BK * g.lda * 2);
     const uint32_t b_step = (uint32_t)((LB == KC) ? TILE_BK * 2 : (int64_t)TILE_BK * g.ldb * 2);

@@ -14,7 +14,8 @@ torch = pytest.importorskip("torch")
 import gpu_util as gu  # noqa: E402
 
 SHAPES = [(256, 256, 256), (512, 384, 640), (300, 72, 136), (1024, 128, 1280), (77, 40, 24), (768, 256, 1152),
-          (520, 264, 384), (384, 264, 136)]   # the last two: tuned interior plus general-kernel strips
+          (520, 264, 384), (384, 264, 136),   # tuned interior plus strips or bands
+          (1000, 256, 384)]                   # wgrad on the tuned kernel with a reduction that is no multiple of 128
 
 
 def P(M, Kl, Nl):

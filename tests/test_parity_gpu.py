@@ -82,7 +82,10 @@ RAGGED = [(1, 8, 8), (1000, 520, 264), (130, 40, 72), (257, 264, 136), (77, 1000
           # outputs that miss the tuned kernel's granularity while the reduction fits it: the library
           # cuts these into a tuned interior and general-kernel strips (fwd; dgrad; wgrad; one strip only)
           (300, 128, 136), (520, 384, 264), (520, 264, 384), (384, 264, 136), (256, 128, 200), (260, 128, 128),
-          (1030, 512, 1160)]
+          (1030, 512, 1160),
+          # token counts (the reduction of wgrad) of any length, odd ones included: the wgrad kernel
+          # rounds the reduction up itself and reads the surplus rows as zeros
+          (1000, 256, 384), (77, 256, 128), (1, 256, 128), (129, 512, 256), (4101, 256, 640), (300, 264, 136)]
 
 
 @pytest.mark.parametrize("M,Kl,Nl", RAGGED)
