@@ -201,3 +201,17 @@ def sample_rows(n_rows: int, tile: int, per_tile: int, seed: int) -> np.ndarray:
         for r in rng.integers(t0, t1, size=per_tile):
             picks.add(int(r))
     return np.array(sorted(picks), dtype=np.int64)
+
+
+def sample_rows_banded(n_rows: int, tile: int, band: int, seed: int) -> np.ndarray:
+    """A stratified, sorted row sample: the first and last row of every `tile`-row block and one
+    seeded row out of every `band` consecutive rows (with tile 256 and band 16: every row band of
+    every matrix-core tile of every workgroup tile is hit)."""
+    rng = np.random.default_rng(seed)
+    picks = set()
+    for t0 in range(0, n_rows, tile):
+        picks.add(t0)
+        picks.add(min(n_rows, t0 + tile) - 1)
+    for b0 in range(0, n_rows, band):
+        picks.add(int(rng.integers(b0, min(n_rows, b0 + band))))
+    return np.array(sorted(picks), dtype=np.int64)

@@ -6,9 +6,21 @@ products of a 3D-tensor-parallel FC layer shard (for the chain workloads: of eve
 axo_layer_step (default; the benchmark's layers have buffers of their own, so the library finds one
 dependence level and runs all products in one grouped launch) or axo_layer_step_ordered (--step
 ordered: one launch per product, in program order).  Inputs are seeded synthetic bf16 shards, resident
-in HBM before the timed region.  Prints one JSON line: TFLOP/s of the step (2*M*Kl*Nl flop per
-product), a roofline object for the dominant kernel (HIP-event timed on the launch stream) and the
-CPU oracle timed on a bounded sample of the same workload.
+in HBM before the timed region.
+
+The headline workload (`value`) is config 3, the MLP up-projection shard with the bias + GELU epilogue:
+with config 4 the largest single-GPU workload of the benchmark.  The same run also times configs
+2, 4 and 5 and reports them under `configs`, each with a roofline object of its own.
+
+Prints one JSON line: TFLOP/s of the step (2*M*Kl*Nl flop per product), a roofline object for the
+dominant kernel (HIP-event timed on the launch stream) and the CPU oracle timed on a bounded sample of
+the headline workload.
+
+Pre-heat: the chip leaves idle at a low clock and needs some hundred milliseconds of load before its power
+controller has settled; a run of `--warmup 5 --steps 20` is 7 ms of GPU time and would be timed on that
+ramp.  Every timed loop is therefore preceded by a time-based pre-heat of the very launch that is
+timed (`--preheat-ms`, default 500 ms of GPU time, reported as `preheat`), then the counted warm-up steps,
+then the timed steps.  The chunk times of the timed region are reported in time order.
 """
 import argparse
 import json
@@ -21,11 +33,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
+PEAK_HBM_GBPS = 8000.0
 
 # HBM-side bytes per launch (fetched + written) of the tuned kernel, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this script, scaled by the same counters' readings for a plain 1 GiB copy
-# (2.000 KiB per FETCH_SIZE count, 1.000 KiB per WRITE_SIZE count).  Keyed by (workload, product);
-# "group" is the single launch of the grouped step.
+# WRITE_SIZE runs of this script (the summaries under profiles/ give the commands), scaled by the same
+# counters' readings for a plain 1 GiB copy (2.000 KiB per FETCH_SIZE count, 1.000 KiB per WRITE_SIZE
+# count).  Keyed by (workload, product); "group" is the single launch of the grouped step.
 MEASURED_TRAFFIC_BYTES = {
     ("cfg2", "fwd"): int((82100.9 * 2.0 + 49152.0) * 1024),
     ("cfg2", "dgrad"): int((98372.0 * 2.0 + 16385.4) * 1024),
@@ -33,18 +46,27 @@ MEASURED_TRAFFIC_BYTES = {
     ("cfg2", "group"): int((305489.7 * 2.0 + 90116.2) * 1024),
 }
 
+HEADLINE = "cfg3"
+ALSO = ("cfg2", "cfg4", "cfg5")
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--config", default="cfg2", help="cfg1..cfg5 (default cfg2, the QKV shard)")
-    ap.add_argument("--all-configs", action="store_true",
-                    help="also time cfg2..cfg5 and gpt20b and report them under 'configs'")
+    ap.add_argument("--config", default=HEADLINE,
+                    help="headline workload: cfg1..cfg5 or gpt20b (default cfg3, the MLP up-projection shard)")
+    ap.add_argument("--only", action="store_true",
+                    help="time the headline workload only (default: the other benchmark configs too, under 'configs')")
+    ap.add_argument("--with-gpt20b", action="store_true",
+                    help="also time the (2,2,4) shards of the paper's GPT-20B running example")
+    ap.add_argument("--preheat-ms", type=float, default=500.0,
+                    help="GPU time of the untimed pre-heat in front of every timed loop (same launches as the loop)")
     ap.add_argument("--step", choices=("layer_step", "ordered"), default="layer_step",
                     help="entry point of the timed step: axo_layer_step (dependence levels, grouped launches; the "
                          "default) or axo_layer_step_ordered (one launch per product, in program order)")
+    ap.add_argument("--no-per-op", action="store_true", help="skip the separate per-product launch loops")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--extras", action="store_true",
                     help="also time the backward-side extras on the largest layer: dgrad through GELU, fp32-accumulating "
@@ -93,50 +115,115 @@ def main() -> int:
 
     step_fn = axo.axo_layer_step_ordered if args.step == "ordered" else axo.axo_layer_step
 
-    def time_step(objs, wsp, nws, steps, warmup):
+    def preheat(fn):
+        """Runs fn back to back until --preheat-ms of GPU time have passed; returns what it did."""
+        info = {"ms": 0.0, "steps": 0}
+        if args.preheat_ms <= 0:
+            return info
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        batch, first = 4, None
+        while info["ms"] < args.preheat_ms and info["steps"] < 1_000_000:
+            e0.record()
+            for _ in range(batch):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            dt = e0.elapsed_time(e1)
+            if first is None:
+                first = dt / batch
+            info["ms"] += dt
+            info["steps"] += batch
+            last = dt / batch
+            # batches of about 25 ms: few synchronisation gaps, and the loop stops close to the target
+            batch = max(1, min(4096, int(25.0 / max(last, 1e-3))))
+        info["ms"] = round(info["ms"], 1)
+        info["first_batch_ms_per_step"] = round(first, 5)
+        info["last_batch_ms_per_step"] = round(last, 5)
+        return info
+
+    def time_loop(fn, steps, warmup):
+        """Pre-heat, `warmup` untimed calls, then exactly `steps` timed calls between two events on the
+        launch stream.  An event per eighth of the run as well (no synchronisation inside the timed
+        region): the chunk times, in time order, show clock drift that the mean hides."""
+        heat = preheat(fn)
         for _ in range(warmup):
-            step_fn(objs, wsp, nws, st)
+            fn()
         torch.cuda.synchronize()
-        # one event per eighth of the run as well (no synchronisation inside the timed region): the
-        # spread between the chunks shows clock drift that the mean hides
         chunk = max(1, steps // 8)
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps // chunk + 1)]
+        e1 = torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
         marks[0].record()
         for i in range(steps):
-            step_fn(objs, wsp, nws, st)
+            fn()
             if (i + 1) % chunk == 0:
                 marks[(i + 1) // chunk].record()
-        e1 = torch.cuda.Event(enable_timing=True)
         e1.record()
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3
-        per_chunk = sorted(marks[k].elapsed_time(marks[k + 1]) / chunk for k in range(steps // chunk))
-        time_step.chunks = {"steps_per_chunk": chunk, "median_ms": round(per_chunk[len(per_chunk) // 2], 5),
-                            "best_ms": round(per_chunk[0], 5), "worst_ms": round(per_chunk[-1], 5)}
-        return max(marks[0].elapsed_time(e1), 0.0) / steps, wall / steps
+        per_chunk = [marks[k].elapsed_time(marks[k + 1]) / chunk for k in range(steps // chunk)]
+        srt = sorted(per_chunk)
+        chunks = {"steps_per_chunk": chunk, "in_time_order_ms": [round(c, 5) for c in per_chunk],
+                  "median_ms": round(srt[len(srt) // 2], 5), "best_ms": round(srt[0], 5),
+                  "worst_ms": round(srt[-1], 5)}
+        return max(marks[0].elapsed_time(e1), 0.0) / steps, wall / steps, chunks, heat
 
-    def time_op(fn, steps, warmup):
-        for _ in range(warmup):
-            fn()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(steps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / steps
-
-    def per_op(L, o, wsp, nws, steps, warmup):
+    def per_op(o, wsp, nws, steps, warmup):
         res = {}
-        res["fwd"] = time_op(lambda: axo.axo_fc_fwd(o.p, o.X, o.ldx, o.W, o.ldw, o.bias, o.epilogue, o.Y, o.ldy,
-                                                    wsp, nws, st), steps, warmup)
-        res["dgrad"] = time_op(lambda: axo.axo_fc_dgrad(o.p, o.dY, o.lddy, o.W, o.ldw, o.dX, o.lddx, wsp, nws, st),
-                               steps, warmup)
-        res["wgrad"] = time_op(lambda: axo.axo_fc_wgrad(o.p, o.X, o.ldx, o.dY, o.lddy, o.dW, o.lddw, wsp, nws, st),
-                               steps, warmup)
+        res["fwd"] = time_loop(lambda: axo.axo_fc_fwd(o.p, o.X, o.ldx, o.W, o.ldw, o.bias, o.epilogue, o.Y, o.ldy,
+                                                      wsp, nws, st), steps, warmup)[0]
+        res["dgrad"] = time_loop(lambda: axo.axo_fc_dgrad(o.p, o.dY, o.lddy, o.W, o.ldw, o.dX, o.lddx, wsp, nws, st),
+                                 steps, warmup)[0]
+        res["wgrad"] = time_loop(lambda: axo.axo_fc_wgrad(o.p, o.X, o.ldx, o.dY, o.lddy, o.dW, o.lddw, wsp, nws, st),
+                                 steps, warmup)[0]
         return res
+
+    def measure(cfg_name, with_per_op):
+        """Times one workload; returns (result dict, state kept for the extras / cpu baseline)."""
+        layers, objs, keep, flop, wsp, nws = setup(cfg_name)
+        ms, wall_ms, chunks, heat = time_loop(lambda: step_fn(objs, wsp, nws, st), args.steps, args.warmup)
+        tflops = flop / (ms * 1e-3) / 1e12
+        li = max(range(len(layers)), key=lambda i: layers[i].flop_per_gemm)
+        gflop = layers[li].flop_per_gemm
+        alg_bytes = sum(2 * (L.shard[0] * L.shard[1] + L.shard[1] * L.shard[2] + L.shard[0] * L.shard[2])
+                        for L in layers)
+        ops = per_op(objs[li], wsp, nws, args.steps, args.warmup) if with_per_op else None
+        grouped = args.step == "layer_step" and 3 * len(layers) <= 12
+        if grouped or ops is None:
+            # the whole step is ONE launch of gemm_group_kernel: its duration is the step's
+            roofline = {"bound": "mfma", "kernel": "gemm_group_kernel (all products of the step in one launch)"
+                        if grouped else "gemm_mixed_kernel (all launches of the step)",
+                        "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(tflops / PEAK_BF16_TFLOPS, 4),
+                        "traffic": MEASURED_TRAFFIC_BYTES.get((cfg_name, "group")) if grouped else None,
+                        "flop_per_launch": flop, "avg_launch_ms": round(ms, 5),
+                        "algorithmic_bytes_per_launch": 3 * alg_bytes}
+        else:
+            # one launch per product: the dominant kernel is the slowest product of the largest layer
+            dom = max(ops, key=ops.get)
+            ach = gflop / (ops[dom] * 1e-3) / 1e12
+            M, Kl, Nl = layers[li].shard
+            roofline = {"bound": "mfma", "kernel": f"gemm_mixed_kernel ({layers[li].name}.{dom})",
+                        "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                        "traffic": MEASURED_TRAFFIC_BYTES.get((cfg_name, dom)), "flop_per_launch": gflop,
+                        "avg_launch_ms": round(ops[dom], 5),
+                        "algorithmic_bytes_per_launch": 2 * (M * Kl + Kl * Nl + M * Nl)}
+        if ops is not None:
+            roofline["separate_launches"] = {
+                "layer": layers[li].name, "per_op_ms": {k: round(v, 5) for k, v in ops.items()},
+                "per_op_tflops": {k: round(gflop / (v * 1e-3) / 1e12, 2) for k, v in ops.items()}}
+        res = {"value": round(tflops, 2), "unit": "TFLOP/s", "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+               "ms_per_step": round(ms, 5), "wall_ms_per_step": round(wall_ms, 5), "ms_per_step_chunks": chunks,
+               "preheat": heat,
+               "config": {"workload": cfg_name,
+                          "step": "axo_layer_step_ordered" if args.step == "ordered" else "axo_layer_step",
+                          "layers": [{"name": L.name, "grid": list(L.grid), "shard_MKN": list(L.shard),
+                                      "epilogue": L.epilogue} for L in layers],
+                          "flop_per_step": flop},
+               "roofline": roofline}
+        state = {"layers": layers, "objs": objs, "keep": keep, "li": li, "wsp": wsp, "nws": nws, "ops": ops}
+        return res, state
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB read + 1 GiB write per copy
@@ -147,97 +234,65 @@ def main() -> int:
         del src, dst
         torch.cuda.empty_cache()
 
-    layers, objs, keep, flop, wsp, nws = setup(args.config)
-    ms, wall_ms = time_step(objs, wsp, nws, args.steps, args.warmup)
-    chunk_stats = dict(time_step.chunks)
-    tflops = flop / (ms * 1e-3) / 1e12
-
-    # per-product launches of the largest layer, each timed in a loop of its own
-    li = max(range(len(layers)), key=lambda i: layers[i].flop_per_gemm)
-    ops = per_op(layers[li], objs[li], wsp, nws, args.steps, args.warmup)
-    gflop = layers[li].flop_per_gemm
-    per_op_info = {"layer": layers[li].name,
-                   "per_op_ms": {k: round(v, 5) for k, v in ops.items()},
-                   "per_op_tflops": {k: round(gflop / (v * 1e-3) / 1e12, 2) for k, v in ops.items()}}
-    alg_bytes = sum(2 * (L.shard[0] * L.shard[1] + L.shard[1] * L.shard[2] + L.shard[0] * L.shard[2]) for L in layers)
-    if args.step == "layer_step" and len(layers) <= 4:
-        # the whole step is ONE launch of gemm_group_kernel: its duration is the step's
-        roofline = {"bound": "mfma", "kernel": "gemm_group_kernel (all products of the step)",
-                    "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(tflops / PEAK_BF16_TFLOPS, 4),
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, "group")), "flop_per_launch": flop,
-                    "avg_launch_ms": round(ms, 5), "algorithmic_bytes_per_launch": 3 * alg_bytes}
-    else:
-        # one launch per product: the dominant kernel is the slowest product of the largest layer
-        dom = max(ops, key=ops.get)
-        ach = gflop / (ops[dom] * 1e-3) / 1e12
-        M, Kl, Nl = layers[li].shard
-        roofline = {"bound": "mfma", "kernel": f"gemm_mixed_kernel ({layers[li].name}.{dom})", "achieved": round(ach, 2),
-                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, dom)), "flop_per_launch": gflop,
-                    "avg_launch_ms": round(ops[dom], 5),
-                    "algorithmic_bytes_per_launch": 2 * (M * Kl + Kl * Nl + M * Nl)}
-    roofline["separate_launches"] = per_op_info
-
-    out = {"metric": "TFLOP/s for fwd+dgrad+wgrad shard GEMMs, 1 MI355X", "value": round(tflops, 2),
+    head, state = measure(args.config, not args.no_per_op)
+    out = {"metric": "TFLOP/s for fwd+dgrad+wgrad shard GEMMs, 1 MI355X", "value": head["value"],
            "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-           "ms_per_step": round(ms, 5), "wall_ms_per_step": round(wall_ms, 5), "ms_per_step_chunks": chunk_stats,
-           "higher_is_better": True,
-           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-           "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
-           "config": {"workload": args.config,
-                      "step": "axo_layer_step_ordered" if args.step == "ordered" else "axo_layer_step", "layers": [
-               {"name": L.name, "grid": list(L.grid), "shard_MKN": list(L.shard), "epilogue": L.epilogue}
-               for L in layers], "flop_per_step": flop},
-           "roofline": roofline}
+           "ms_per_step": head["ms_per_step"], "wall_ms_per_step": head["wall_ms_per_step"],
+           "ms_per_step_chunks": head["ms_per_step_chunks"], "preheat": head["preheat"],
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "frac_of_bf16_mfma_peak": head["frac_of_bf16_mfma_peak"],
+           "config": head["config"], "roofline": head["roofline"]}
 
+    layers, objs, li, wsp, nws, ops = (state[k] for k in ("layers", "objs", "li", "wsp", "nws", "ops"))
     if args.extras:
         L, o = layers[li], objs[li]
+        gflop = L.flop_per_gemm
         M, Kl, Nl = L.shard
         pre = torch.randn((M, Kl), device="cuda:0").to(torch.bfloat16).view(torch.int16)
         dW32 = torch.zeros((Kl, Nl), dtype=torch.float32, device="cuda:0")
         db = torch.zeros((Nl,), dtype=torch.float32, device="cuda:0")
-        t_da = time_op(lambda: axo.axo_fc_dgrad_act(o.p, o.dY, o.lddy, o.W, o.ldw, pre.data_ptr(), Kl,
-                                                    axo.AXO_EPI_BIAS_GELU_TANH, o.dX, o.lddx, wsp, nws, st),
-                       args.steps, args.warmup)
-        t_wa = time_op(lambda: axo.axo_fc_wgrad_acc(o.p, o.X, o.ldx, o.dY, o.lddy, dW32.data_ptr(), Nl, wsp, nws, st),
-                       args.steps, args.warmup)
-        t_bg = time_op(lambda: axo.axo_bias_grad(o.p, o.dY, o.lddy, db.data_ptr(), 0, st), args.steps, args.warmup)
+        t_fw = ops["fwd"] if ops else time_loop(
+            lambda: axo.axo_fc_fwd(o.p, o.X, o.ldx, o.W, o.ldw, o.bias, o.epilogue, o.Y, o.ldy, wsp, nws, st),
+            args.steps, args.warmup)[0]
+        t_da = time_loop(lambda: axo.axo_fc_dgrad_act(o.p, o.dY, o.lddy, o.W, o.ldw, pre.data_ptr(), Kl,
+                                                      axo.AXO_EPI_BIAS_GELU_TANH, o.dX, o.lddx, wsp, nws, st),
+                         args.steps, args.warmup)[0]
+        t_wa = time_loop(lambda: axo.axo_fc_wgrad_acc(o.p, o.X, o.ldx, o.dY, o.lddy, dW32.data_ptr(), Nl, wsp, nws, st),
+                         args.steps, args.warmup)[0]
+        t_bg = time_loop(lambda: axo.axo_bias_grad(o.p, o.dY, o.lddy, db.data_ptr(), 0, st), args.steps, args.warmup)[0]
         bg_bytes = 2 * M * Nl + 4 * Nl
         # the whole local step of that layer with all extras, through the scheduled chain entry point
         ext = [axo.LayerExt.make(o, pre=pre.data_ptr(), ldpre=Kl, act_below=axo.AXO_EPI_BIAS_GELU_TANH,
                                  dW32=dW32.data_ptr(), lddw32=Nl, db=db.data_ptr(), accumulate_db=0)]
-        t_ext = time_op(lambda: axo.axo_layer_step_ext(ext, wsp, nws, st), args.steps, args.warmup)
+        t_ext = time_loop(lambda: axo.axo_layer_step_ext(ext, wsp, nws, st), args.steps, args.warmup)[0]
         out["extras"] = {
             "layer_step_ext": {"ms": round(t_ext, 5), "tflops": round(3 * gflop / (t_ext * 1e-3) / 1e12, 2),
                                "what": "fwd + dgrad through GELU + fp32-accumulating wgrad + bias gradient, one call",
-                               "separate_calls_ms": round(ops["fwd"] + t_da + t_wa + t_bg, 5)},
+                               "separate_calls_ms": round(t_fw + t_da + t_wa + t_bg, 5)},
             "layer": L.name,
-            "dgrad_gelu_tanh": {"ms": round(t_da, 5), "tflops": round(gflop / (t_da * 1e-3) / 1e12, 2),
-                                "plain_dgrad_ms": round(ops["dgrad"], 5)},
-            "wgrad_acc_f32": {"ms": round(t_wa, 5), "tflops": round(gflop / (t_wa * 1e-3) / 1e12, 2),
-                              "plain_wgrad_ms": round(ops["wgrad"], 5)},
+            "dgrad_gelu_tanh": {"ms": round(t_da, 5), "tflops": round(gflop / (t_da * 1e-3) / 1e12, 2)},
+            "wgrad_acc_f32": {"ms": round(t_wa, 5), "tflops": round(gflop / (t_wa * 1e-3) / 1e12, 2)},
             "bias_grad": {"ms": round(t_bg, 5), "bound": "hbm", "algorithmic_bytes": bg_bytes,
-                          "achieved_GBps": round(bg_bytes / (t_bg * 1e-3) / 1e9, 1), "peak_GBps": 8000.0,
-                          "frac": round(bg_bytes / (t_bg * 1e-3) / 1e9 / 8000.0, 4)}}
+                          "achieved_GBps": round(bg_bytes / (t_bg * 1e-3) / 1e9, 1), "peak_GBps": PEAK_HBM_GBPS,
+                          "frac": round(bg_bytes / (t_bg * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4)}}
+        del pre, dW32, db, ext
 
-    if args.all_configs:
-        extra = {}
-        for name in ("cfg2", "cfg3", "cfg4", "cfg5", "gpt20b"):
-            if name == args.config:
-                extra[name] = {"tflops": round(tflops, 2), "ms_per_step": round(ms, 5)}
-                continue
-            del keep
+    head_layer = layers[li]
+    del state, objs, layers
+    if not args.only:
+        names = [n for n in ALSO + (("gpt20b",) if args.with_gpt20b else ()) if n != args.config]
+        others = {}
+        for name in names:
             torch.cuda.empty_cache()
-            l2, o2, keep, f2, w2, n2 = setup(name)
-            m2, _ = time_step(o2, w2, n2, args.steps, args.warmup)
-            extra[name] = {"tflops": round(f2 / (m2 * 1e-3) / 1e12, 2), "ms_per_step": round(m2, 5),
-                           "frac_of_peak": round(f2 / (m2 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
-        out["configs"] = extra
+            res, s2 = measure(name, False)
+            del s2
+            others[name] = {k: res[k] for k in ("value", "unit", "frac_of_bf16_mfma_peak", "ms_per_step",
+                                                "ms_per_step_chunks", "preheat", "config", "roofline")}
+        out["configs"] = others
 
     if not args.no_cpu_baseline:
         import oracle  # test infrastructure; only this baseline leg uses it
-        L = layers[li]
+        L = head_layer
         d = syn.layer_inputs(L)
         M, Kl, Nl = L.shard
         # the oracle runs about 60 GFLOP/s on 16 cores: bound the sample to roughly 10-20 s of CPU work
@@ -255,7 +310,7 @@ def main() -> int:
         cflop = 2.0 * (2 * n_act * Kl * Nl + n_w * M * Nl)
         out["cpu_baseline"] = {"value": round(cflop / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
                                "kind": "oracle", "seconds": round(dt, 2),
-                               "sample": f"{L.name}: {n_act} of {M} output rows of fwd and of dgrad, "
+                               "sample": f"{args.config} {L.name}: {n_act} of {M} output rows of fwd and of dgrad, "
                                          f"{n_w} of {Kl} rows of dW (fp64 plain loops)"}
     print(json.dumps(out), flush=True)
     return 0

@@ -113,6 +113,23 @@ int axo_shard_dims(const axo_problem_t *p, int64_t *M, int64_t *Kl, int64_t *Nl,
  * Returns 0 for an invalid problem (the op call itself reports the error). */
 size_t axo_workspace_bytes(const axo_problem_t *p, int op);
 
+/* Which kernels a product takes, as axo_fc_route reports it. */
+typedef enum axo_route {
+    AXO_ROUTE_NONE = 0,            /* an empty output: nothing is launched                                 */
+    AXO_ROUTE_TILED = 1,           /* the tuned MFMA kernel, one launch                                    */
+    AXO_ROUTE_COVERED = 2,         /* a ragged output covered with whole (overlapping) tuned tiles         */
+    AXO_ROUTE_INTERIOR_STRIPS = 3, /* the interior on the tuned kernel, leftover strips on the general one */
+    AXO_ROUTE_GENERAL = 4          /* the general (bounds-checked, untuned) kernel                         */
+} axo_route_t;
+
+/* Host only.  Reports in *route (axo_route_t) which kernels the product `op` (axo_op_t) of this
+ * problem takes when its two inputs have leading dimensions ld_a, ld_b (in the argument order of the
+ * product's entry point: X, W for forward; dY, W for dgrad; X, dY for wgrad) and its output ld_out.
+ * The choice depends on the shard shape and on the leading dimensions only (the tuned kernel forms
+ * 32-bit byte offsets inside an operand tile), never on data.  For capacity planning and tests.
+ * Errors: those of the product's argument checks; NULL_PTR (route); BAD_ARG (unknown op). */
+int axo_fc_route(const axo_problem_t *p, int op, int64_t ld_a, int64_t ld_b, int64_t ld_out, int *route);
+
 /* Forward local product  Y[M x Nl] = epilogue( X[M x Kl] . W[Kl x Nl] ).
  * X, W, Y: device pointers, bf16, row-major, 16-byte aligned; ldx >= Kl, ldw >= Nl, ldy >= Nl,
  * each a multiple of 8.  bias: device pointer to Nl bf16 values (16-byte aligned) or NULL when

@@ -171,6 +171,33 @@ def compare_bf16(cand_bits: np.ndarray, ref: np.ndarray, per_elem_tol: float = 1
     return {"rel_fro": float(res[0]), "max_rel_row": float(res[1]), "n_bad": int(res[2]), "n_nonfinite": int(res[3])}
 
 
+def rne_bf16_bits(ref: np.ndarray) -> np.ndarray:
+    """fp64 values rounded once, to nearest with ties to even, to bf16 bit patterns (the rounding the
+    benchmark's north star asks of the store).  fp64 -> fp32 is done with round-to-odd (truncate
+    towards zero, then set the last mantissa bit if anything was lost), which makes the second
+    rounding, fp32 -> bf16 nearest-even on the bit pattern, equal to a single direct rounding.
+    Finite inputs inside the fp32 range."""
+    x = np.ascontiguousarray(ref, dtype=np.float64)
+    with np.errstate(over="ignore", under="ignore"):
+        f = x.astype(np.float32)
+    fd = f.astype(np.float64)
+    inexact = fd != x
+    away = np.abs(fd) > np.abs(x)                      # the nearest fp32 lies beyond x: step back towards zero
+    t = np.where(inexact & away, np.nextafter(f, np.float32(0.0)), f).astype(np.float32)
+    u = t.view(np.uint32) | inexact.astype(np.uint32)  # round to odd
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    return ((u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)).astype(np.uint16)
+
+
+def ulp_distance_bf16(cand_bits: np.ndarray, ref: np.ndarray) -> np.ndarray:
+    """How many bf16 values lie between each candidate and the oracle value rounded once to bf16
+    (0 = the correctly rounded result; +0 and -0 count as the same value).  Finite values."""
+    def ordinal(b):
+        b = np.asarray(b, dtype=np.uint16).astype(np.int32)
+        return np.where(b < 0x8000, b, -(b & 0x7FFF))
+    return np.abs(ordinal(cand_bits) - ordinal(rne_bf16_bits(ref)))
+
+
 # ---------------------------------------------------------------------------
 # Grid decomposition (Section 3.2; Algorithm 1 for the reduce axes)
 # ---------------------------------------------------------------------------

@@ -16,6 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libaxo.so")
 
 AXO_EPI_NONE, AXO_EPI_BIAS, AXO_EPI_BIAS_GELU_TANH, AXO_EPI_BIAS_GELU_ERF = 0, 1, 2, 3
 AXO_OP_FWD, AXO_OP_DGRAD, AXO_OP_WGRAD = 0, 1, 2
+AXO_ROUTE_NONE, AXO_ROUTE_TILED, AXO_ROUTE_COVERED, AXO_ROUTE_INTERIOR_STRIPS, AXO_ROUTE_GENERAL = 0, 1, 2, 3, 4
 
 
 class AxoError(RuntimeError):
@@ -89,6 +90,8 @@ def library() -> ctypes.CDLL:
     L.axo_shard_dims.restype = i32
     L.axo_workspace_bytes.argtypes = [PP, i32]
     L.axo_workspace_bytes.restype = sz
+    L.axo_fc_route.argtypes = [PP, i32, i64, i64, i64, ctypes.POINTER(ctypes.c_int)]
+    L.axo_fc_route.restype = i32
     L.axo_fc_fwd.argtypes = [PP, vp, i64, vp, i64, vp, i32, vp, i64, vp, sz, vp]
     L.axo_fc_fwd.restype = i32
     L.axo_fc_dgrad.argtypes = [PP, vp, i64, vp, i64, vp, i64, vp, sz, vp]
@@ -140,6 +143,14 @@ def axo_shard_dims(p: Optional[Problem], check: bool = True):
 
 def axo_workspace_bytes(p: Problem, op: int) -> int:
     return int(library().axo_workspace_bytes(ctypes.byref(p), int(op)))
+
+
+def axo_fc_route(p: Problem, op: int, ld_a: int, ld_b: int, ld_out: int, check: bool = True) -> Tuple[int, int]:
+    """(status, axo_route_t): which kernels the product takes for these leading dimensions."""
+    r = ctypes.c_int(-1)
+    rc = library().axo_fc_route(ctypes.byref(p) if p is not None else None, int(op), ld_a, ld_b, ld_out,
+                                ctypes.byref(r))
+    return _check(rc, "axo_fc_route", check), int(r.value)
 
 
 def axo_fc_fwd(p: Problem, X: int, ldx: int, W: int, ldw: int, bias: Optional[int], epilogue: int, Y: int,

@@ -90,8 +90,8 @@ constexpr double SMALL_TILE_COST = 0.60;
 // The tuned kernel addresses an operand tile through a buffer descriptor with 32-bit byte offsets:
 // the span a workgroup walks (256 rows of a KC operand, or the whole reduction of an MC operand)
 // has to stay below 4 GiB.
-bool span_ok(int layout, int64_t ld, int R) {
-    const int64_t elems = layout == axo::KC ? 256 * ld + R : (int64_t)R * ld + 256;
+bool span_ok(int layout, int64_t ld, int64_t R) {
+    const int64_t elems = layout == axo::KC ? 256 * ld + R : R * ld + 256;
     return elems * 2 < (int64_t)0xFFFF0000;
 }
 
@@ -100,8 +100,13 @@ bool span_ok(int layout, int64_t ld, int R) {
 // length up itself and reads the surplus rows as zeros, so any length goes.
 bool tileable(const GemmArgs& g, int la, int lb) {
     const bool any_reduction = la == axo::MC && lb == axo::MC;
-    return g.R > 0 && (any_reduction || g.R % (2 * axo::TILE_BK) == 0) && g.Mo > 0 && g.No > 0 && g.Mo % 256 == 0 &&
-           g.No % 128 == 0 && span_ok(la, g.lda, g.R) && span_ok(lb, g.ldb, g.R);
+    if (!(g.R > 0 && (any_reduction || g.R % (2 * axo::TILE_BK) == 0) && g.Mo > 0 && g.No > 0 && g.Mo % 256 == 0 &&
+          g.No % 128 == 0))
+        return false;
+    // the span is that of the rows the kernel walks: the reduction rounded up to the unrolled loop's
+    // 128 (the surplus rows of wgrad read as zeros, but their offsets are still formed in 32 bits)
+    const int64_t walked = ((int64_t)g.R + 2 * axo::TILE_BK - 1) / (2 * axo::TILE_BK) * (2 * axo::TILE_BK);
+    return span_ok(la, g.lda, walked) && span_ok(lb, g.ldb, walked);
 }
 
 // Time (in big-tile units) a greedy dispatch of n_big big tiles followed by n_small small tiles
@@ -407,32 +412,42 @@ bool cover_with_tiles(const Plan& pl, std::vector<Plan>* out) {
 // launch when only the output's granularity is in the way (measured on 4096 x 2048 x 6152, eight
 // columns over: 198 TFLOP/s through the general kernel alone); failing that, the interior on the
 // tuned kernel and the leftover strips on the general one; the general kernel for the rest.
-int launch(const GemmArgs& g, int la, int lb, hipStream_t st) {
-    if (g.Mo == 0 || g.No == 0) return AXO_OK;
-    if (tileable(g, la, lb)) return launch_tile_layout(g, la, lb, st);
+int route_of(const GemmArgs& g, int la, int lb, std::vector<Plan>* pieces) {
+    if (g.Mo == 0 || g.No == 0) return AXO_ROUTE_NONE;
+    if (tileable(g, la, lb)) return AXO_ROUTE_TILED;
     Plan whole;
     whole.g = g;
     whole.la = la;
     whole.lb = lb;
-    std::vector<Plan> pieces;
-    if (cover_with_tiles(whole, &pieces)) {
-        const Plan* ptr[4];
-        for (size_t i = 0; i < pieces.size(); ++i) ptr[i] = &pieces[i];
-        return launch_group(ptr, (int)pieces.size(), st);
-    }
+    if (cover_with_tiles(whole, pieces)) return AXO_ROUTE_COVERED;
     const int Mi = g.Mo / 256 * 256, Ni = g.No / 128 * 128;
-    if (Mi > 0 && Ni > 0) {
-        const GemmArgs interior = sub_product(g, la, lb, 0, Mi, 0, Ni);
-        // block offsets that are multiples of 256 rows and 128 columns keep every alignment
-        if (tileable(interior, la, lb)) {
-            int rc = launch_tile_layout(interior, la, lb, st);
+    // block offsets that are multiples of 256 rows and 128 columns keep every alignment
+    if (Mi > 0 && Ni > 0 && tileable(sub_product(g, la, lb, 0, Mi, 0, Ni), la, lb)) return AXO_ROUTE_INTERIOR_STRIPS;
+    return AXO_ROUTE_GENERAL;
+}
+
+int launch(const GemmArgs& g, int la, int lb, hipStream_t st) {
+    std::vector<Plan> pieces;
+    switch (route_of(g, la, lb, &pieces)) {
+        case AXO_ROUTE_NONE: return AXO_OK;
+        case AXO_ROUTE_TILED: return launch_tile_layout(g, la, lb, st);
+        case AXO_ROUTE_COVERED: {
+            const Plan* ptr[4];
+            for (size_t i = 0; i < pieces.size(); ++i) ptr[i] = &pieces[i];
+            return launch_group(ptr, (int)pieces.size(), st);
+        }
+        case AXO_ROUTE_INTERIOR_STRIPS: {
+            const int Mi = g.Mo / 256 * 256, Ni = g.No / 128 * 128;
+            int rc = launch_tile_layout(sub_product(g, la, lb, 0, Mi, 0, Ni), la, lb, st);
             if (rc == AXO_OK && g.No > Ni) rc = launch_generic(sub_product(g, la, lb, 0, g.Mo, Ni, g.No - Ni), la, lb, st);
             if (rc == AXO_OK && g.Mo > Mi) rc = launch_generic(sub_product(g, la, lb, Mi, g.Mo - Mi, 0, Ni), la, lb, st);
             return rc;
         }
+        default: return launch_generic(g, la, lb, st);
     }
-    return launch_generic(g, la, lb, st);
 }
+
+int check_no_alias(const Plan& pl);  // defined with the byte-range code below
 
 int plan_fwd(const axo_problem_t* p, const void* X, int64_t ldx, const void* W, int64_t ldw, const void* bias,
              int epilogue, void* Y, int64_t ldy, void* ws, size_t ws_bytes, Plan* out) {
@@ -456,7 +471,7 @@ int plan_fwd(const axo_problem_t* p, const void* X, int64_t ldx, const void* W, 
     g.epilogue = epilogue;
     g.add_bias = (epilogue != AXO_EPI_NONE && s.k_coord == 0) ? 1 : 0;
     out->la = axo::KC; out->lb = axo::MC;
-    return AXO_OK;
+    return check_no_alias(*out);
 }
 
 int plan_dgrad(const axo_problem_t* p, const void* dY, int64_t lddy, const void* W, int64_t ldw, void* dX,
@@ -477,7 +492,7 @@ int plan_dgrad(const axo_problem_t* p, const void* dY, int64_t lddy, const void*
     g.Mo = (int)s.M; g.No = (int)s.Kl; g.R = (int)s.Nl;
     g.epilogue = AXO_EPI_NONE; g.add_bias = 0;
     out->la = axo::KC; out->lb = axo::KC;
-    return AXO_OK;
+    return check_no_alias(*out);
 }
 
 int plan_wgrad(const axo_problem_t* p, const void* X, int64_t ldx, const void* dY, int64_t lddy, void* dW,
@@ -498,7 +513,7 @@ int plan_wgrad(const axo_problem_t* p, const void* X, int64_t ldx, const void* d
     g.Mo = (int)s.Kl; g.No = (int)s.Nl; g.R = (int)s.M;
     g.epilogue = AXO_EPI_NONE; g.add_bias = 0;
     out->la = axo::MC; out->lb = axo::MC;
-    return AXO_OK;
+    return check_no_alias(*out);
 }
 
 int plan_bias_grad(const axo_problem_t* p, const void* dY, int64_t lddy, float* db, int accumulate, Plan* out) {
@@ -517,7 +532,7 @@ int plan_bias_grad(const axo_problem_t* p, const void* dY, int64_t lddy, float* 
     if (s.Nl == 0) return AXO_OK;
     if (!db) return AXO_ERR_NULL_PTR;
     if (reinterpret_cast<uintptr_t>(db) & 3u) return AXO_ERR_MISALIGNED;
-    return AXO_OK;
+    return check_no_alias(*out);
 }
 
 int launch_bias_grad(const axo::BiasGradArgs& g, hipStream_t st) {
@@ -571,7 +586,7 @@ int plan_dgrad_act(const axo_problem_t* p, const void* dY, int64_t lddy, const v
     out->g.aux = static_cast<const axo::bf16_t*>(pre);
     out->g.ldaux = ldpre;
     out->g.epilogue = act == AXO_EPI_BIAS_GELU_TANH ? axo::EPI_MUL_DGELU_TANH : axo::EPI_MUL_DGELU_ERF;
-    return AXO_OK;
+    return check_no_alias(*out);
 }
 
 // wgrad accumulated into an fp32 matrix (see axo_fc_wgrad_acc)
@@ -591,7 +606,7 @@ int plan_wgrad_acc(const axo_problem_t* p, const void* X, int64_t ldx, const voi
     out->g.C = reinterpret_cast<axo::bf16_t*>(dW32);
     out->g.ldc = lddw;
     out->g.epilogue = axo::EPI_ACC_F32;
-    return AXO_OK;
+    return check_no_alias(*out);
 }
 
 // The chain of axo_layer_step_ext: 3 or 4 units per layer, in program order.
@@ -639,15 +654,37 @@ int plan_chain_ext(const axo_layer_ext_t* layers, int n_layers, void* ws, size_t
 
 // ---- dependence analysis of a chain --------------------------------------------------------
 // Byte range [lo, hi) that a matrix argument covers (rows x row_len elements of elem bytes, rows
-// ld elements apart); empty matrices cover nothing.
+// ld elements apart); empty matrices cover nothing.  The matrix itself is kept beside its range
+// for the exact overlap test.
 struct Range {
     uintptr_t lo, hi;
+    int64_t pitch, rows, width;  // bytes between rows, row count, bytes per row
     bool overlaps(const Range& o) const { return lo < o.hi && o.lo < hi; }
+    // Do the two matrices share a byte?  (Ranges that overlap need not: two column blocks of one
+    // buffer interleave.)  Row r of this matrix covers [a, a + width) relative to the other's
+    // base; row q of the other covers [q * pitch, q * pitch + width_o); they meet iff
+    // q * pitch < a + width and q * pitch + width_o > a, an interval of q that is clamped to the
+    // other's rows.  Only called when the ranges overlap, which no well-formed call makes them do.
+    bool shares_bytes_with(const Range& o) const {
+        if (!overlaps(o)) return false;
+        auto floor_div = [](int64_t x, int64_t y) { return x / y - ((x % y != 0) && ((x < 0) != (y < 0)) ? 1 : 0); };
+        const int64_t op = o.rows > 1 ? o.pitch : (int64_t)(o.hi - o.lo) + 1;  // one row: any positive pitch
+        for (int64_t r = 0; r < rows; ++r) {
+            const int64_t a = (int64_t)(lo - o.lo) + r * pitch;
+            const int64_t q_hi = std::min<int64_t>(floor_div(a + width - 1, op), o.rows - 1);
+            const int64_t q_lo = std::max<int64_t>(floor_div(a - o.width, op) + 1, 0);
+            if (q_lo <= q_hi) return true;
+        }
+        return false;
+    }
 };
 bool matrix_range(const void* ptr, int64_t ld, int64_t rows, int64_t row_len, int elem, Range* r) {
     if (!ptr || rows <= 0 || row_len <= 0) return false;
     r->lo = reinterpret_cast<uintptr_t>(ptr);
     r->hi = r->lo + (uintptr_t)(((rows - 1) * ld + row_len) * elem);
+    r->pitch = ld * elem;
+    r->rows = rows;
+    r->width = row_len * elem;
     return true;
 }
 // What one product reads and writes.  (Ranges, not elements: two column blocks interleaved in one
@@ -655,7 +692,7 @@ bool matrix_range(const void* ptr, int64_t ld, int64_t rows, int64_t row_len, in
 struct Footprint {
     Range in[4];
     int n_in = 0;
-    Range out{0, 0};
+    Range out{0, 0, 0, 0, 0};
     bool has_out = false;
     bool conflicts_with_later(const Footprint& later) const {
         if (has_out) {
@@ -666,6 +703,13 @@ struct Footprint {
         if (later.has_out)
             for (int k = 0; k < n_in; ++k)
                 if (in[k].overlaps(later.out)) return true;                            // write after read
+        return false;
+    }
+    // the output shares bytes with one of the product's own inputs
+    bool output_aliases_input() const {
+        if (!has_out) return false;
+        for (int k = 0; k < n_in; ++k)
+            if (out.shares_bytes_with(in[k])) return true;
         return false;
     }
 };
@@ -689,6 +733,11 @@ Footprint footprint(const Plan& pl) {
     f.has_out = matrix_range(g.C, g.ldc, g.Mo, g.No, g.epilogue == axo::EPI_ACC_F32 ? 4 : 2, &f.out);
     return f;
 }
+// The rule of the header, checked: an output that shares bytes with an input of its own product is
+// refused.  The kernels write an output tile while other workgroups still read the operands, and
+// a ragged output is covered with overlapping tiles that are computed twice, so an in-place call
+// (say dX written over the pre-activation it is multiplied with) would silently go wrong.
+int check_no_alias(const Plan& pl) { return footprint(pl).output_aliases_input() ? AXO_ERR_BAD_ARG : AXO_OK; }
 // Dependence level of every product of a chain given in program order: 0 when it conflicts with
 // no earlier product, otherwise one more than the highest level among the earlier products it
 // conflicts with.  Products of one level are independent of each other, and every product a
@@ -841,6 +890,25 @@ size_t axo_workspace_bytes(const axo_problem_t* p, int op) {
     if (derive_shard(p, &s) != AXO_OK) return 0;
     if (op < AXO_OP_FWD || op > AXO_OP_WGRAD) return 0;
     return 0;  // no product needs workspace at present; the argument is kept for split reductions
+}
+
+int axo_fc_route(const axo_problem_t* p, int op, int64_t ld_a, int64_t ld_b, int64_t ld_out, int* route) {
+    return guarded([&]() -> int {
+        if (!route) return AXO_ERR_NULL_PTR;
+        if (op < AXO_OP_FWD || op > AXO_OP_WGRAD) return AXO_ERR_BAD_ARG;
+        // made-up, well-separated and aligned addresses: the planners compare pointers, never follow them
+        const void* a = reinterpret_cast<const void*>((uintptr_t)1 << 40);
+        const void* b = reinterpret_cast<const void*>((uintptr_t)2 << 40);
+        void* c = reinterpret_cast<void*>((uintptr_t)3 << 40);
+        Plan pl;
+        const int rc = op == AXO_OP_FWD     ? plan_fwd(p, a, ld_a, b, ld_b, nullptr, AXO_EPI_NONE, c, ld_out, nullptr, 0, &pl)
+                       : op == AXO_OP_DGRAD ? plan_dgrad(p, a, ld_a, b, ld_b, c, ld_out, nullptr, 0, &pl)
+                                            : plan_wgrad(p, a, ld_a, b, ld_b, c, ld_out, nullptr, 0, &pl);
+        if (rc) return rc;
+        std::vector<Plan> pieces;
+        *route = route_of(pl.g, pl.la, pl.lb, &pieces);
+        return AXO_OK;
+    });
 }
 
 int axo_fc_fwd(const axo_problem_t* p, const void* X, int64_t ldx, const void* W, int64_t ldw, const void* bias,

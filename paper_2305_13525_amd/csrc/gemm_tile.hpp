@@ -322,13 +322,12 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     // to write LDS it puts a full vmcnt(0) wait in front of every later transposing LDS read,
     // which stalls the wave for a whole memory latency in every step.  The kernel keeps the
     // ordering itself: the vmcnt(0) wait and the barrier before the last MFMA group of each step.
-    // M0 is written here without being declared: it is a reserved register that the compiler
-    // never allocates and only sets itself right before instructions that read it (LDS-DMA and
-    // lane-indexed moves), none of which this kernel makes it generate.
+    // M0 (the LDS destination of the load) is an input operand bound to the physical register, so
+    // the compiler writes it itself and knows what the statement reads.
     auto load_lds = [](uint32_t lds_dst, uint32_t off, u32x4_t rsrc, uint32_t soff) __attribute__((always_inline)) {
-        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+        asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds"
                      :
-                     : "s"(lds_dst), "v"(off), "s"(rsrc), "s"(soff)
+                     : "v"(off), "s"(rsrc), "s"(soff), "{m0}"(lds_dst)
                      : "memory");
     };
     // Loads LO..HI-1 of the NL loads that fill stage s with the step at (a_soff, b_soff): the A
@@ -420,15 +419,18 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     // ---- epilogue: acc[a][b][e] is C[i0 + wm*WTM + a*16 + lane%16][j0 + wn*WTN + b*16 + 4*(lane/16) + e]
     __syncthreads();  // all waves are done reading the operand buffers
     char* stage = smem + wave * (C::WTM * C::EPI_STRIDE);
-    // the epilogue kind is decided once, outside the element loops: the plain path is then
+    // The epilogue kind is decided once, outside the element loops: the plain path is then
     // straight-line code (the activation code is large; branching around it per element made the
-    // epilogue several times slower than the stores it feeds)
-    // Origin of the wave tile in the output.  Pinned in scalar registers ahead of the epilogue
-    // switch: when the compiler was left to rematerialise these sums inside each branch, one
-    // branch of the three-way dgrad switch came out without the column term (it stayed undefined
-    // on that path in the generated code) and the stores that follow the switch went astray.
+    // epilogue several times slower than the stores it feeds).  Every branch of that decision is
+    // a complete epilogue, stores included; whatever the branches share (the wave tile's origin,
+    // the output pointer) is formed here, ahead of the decision, with the origin pinned in scalar
+    // registers, so no branch has a version of its own to merge afterwards.  (An earlier form
+    // computed the origin behind a three-way switch; the generated code of one dgrad branch then
+    // lacked the upper half of the 64-bit column offset and the stores went astray.  Positional,
+    // bit-exact tests of every epilogue kind on both tile sizes guard this.)
     int wrow0 = i0 + wm * C::WTM, wcol0 = j0 + wn * C::WTN;
     asm volatile("" : "+s"(wrow0), "+s"(wcol0));
+    bf16_t* const Cw = g.C + (int64_t)wrow0 * g.ldc + wcol0;
     auto convert_and_stage = [&](auto epi_tag) __attribute__((always_inline)) {
         constexpr int EPI = decltype(epi_tag)::value;
         constexpr bool FWD_EPI = EPI >= EPI_BIAS && EPI <= EPI_BIAS_GELU_ERF;
@@ -469,19 +471,49 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
             }
         }
     };
+    // The staged sub-tile out to memory as full row segments of 16 bytes per lane.
+    auto store_staged = [&]() __attribute__((always_inline)) {
+        // the staging region is private to the wave: only wave-level ordering is needed
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+        __builtin_amdgcn_wave_barrier();
+        constexpr int LANES_PER_ROW = C::WTN * 2 / 16;
+        constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
+        // All reads are issued before the first store: interleaved one by one (as the compiler
+        // orders them when left alone) every store waits for its own LDS read, and the 16 round
+        // trips cost more than the stores themselves (measured 5000 cycles for the slower wave of
+        // each SIMD).  The accumulators are dead by now, so the registers are free.
+        constexpr int PASSES = C::WTM / ROWS_PER_PASS;
+        u32x4 vdat[PASSES];
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int row = p * ROWS_PER_PASS + lane / LANES_PER_ROW, ch = lane % LANES_PER_ROW;
+            vdat[p] = *reinterpret_cast<const u32x4*>(stage + row * C::EPI_STRIDE + ch * 16);
+        }
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int row = p * ROWS_PER_PASS + lane / LANES_PER_ROW, ch = lane % LANES_PER_ROW;
+            // non-temporal: the output is not read again by this launch, and a workgroup cannot retire
+            // before its stores are acknowledged
+            __builtin_nontemporal_store(vdat[p], reinterpret_cast<u32x4*>(Cw + (int64_t)row * g.ldc + ch * 8));
+        }
+    };
+    auto finish = [&](auto epi_tag) __attribute__((always_inline)) {
+        convert_and_stage(epi_tag);
+        store_staged();
+    };
     // Each product has its own epilogue kinds, so each layout pair compiles only those.
     if (LA == KC && LB == MC) {  // forward
         switch (g.epilogue) {
-            case EPI_NONE: convert_and_stage(IC<EPI_NONE>{}); break;
-            case EPI_BIAS: convert_and_stage(IC<EPI_BIAS>{}); break;
-            case EPI_BIAS_GELU_TANH: convert_and_stage(IC<EPI_BIAS_GELU_TANH>{}); break;
-            default: convert_and_stage(IC<EPI_BIAS_GELU_ERF>{}); break;
+            case EPI_NONE: finish(IC<EPI_NONE>{}); return;
+            case EPI_BIAS: finish(IC<EPI_BIAS>{}); return;
+            case EPI_BIAS_GELU_TANH: finish(IC<EPI_BIAS_GELU_TANH>{}); return;
+            default: finish(IC<EPI_BIAS_GELU_ERF>{}); return;
         }
     } else if (LA == KC && LB == KC) {  // dgrad
         switch (g.epilogue) {
-            case EPI_NONE: convert_and_stage(IC<EPI_NONE>{}); break;
-            case EPI_MUL_DGELU_TANH: convert_and_stage(IC<EPI_MUL_DGELU_TANH>{}); break;
-            default: convert_and_stage(IC<EPI_MUL_DGELU_ERF>{}); break;
+            case EPI_NONE: finish(IC<EPI_NONE>{}); return;
+            case EPI_MUL_DGELU_TANH: finish(IC<EPI_MUL_DGELU_TANH>{}); return;
+            default: finish(IC<EPI_MUL_DGELU_ERF>{}); return;
         }
     } else {  // wgrad
         if (g.epilogue == EPI_ACC_F32) {
@@ -497,35 +529,7 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
                 }
             return;
         }
-        convert_and_stage(IC<EPI_NONE>{});
-    }
-    // the staging region is private to the wave: only wave-level ordering is needed
-    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-    __builtin_amdgcn_wave_barrier();
-    constexpr int LANES_PER_ROW = C::WTN * 2 / 16;
-    constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
-    bf16_t* Cw = g.C + (int64_t)wrow0 * g.ldc + wcol0;
-    // All reads of a batch are issued before its first store: interleaved one by one (as the
-    // compiler orders them when left alone) every store waits for its own LDS read, and the 16
-    // round trips cost more than the stores themselves (measured 5000 cycles for the slower wave
-    // of each SIMD).  The accumulators are dead by now, so the registers are free.
-    constexpr int PASSES = C::WTM / ROWS_PER_PASS, BATCH = PASSES;
-    static_assert(PASSES % BATCH == 0, "whole batches");
-#pragma unroll
-    for (int p0 = 0; p0 < PASSES; p0 += BATCH) {
-        u32x4 vdat[BATCH];
-#pragma unroll
-        for (int p = 0; p < BATCH; ++p) {
-            const int row = (p0 + p) * ROWS_PER_PASS + lane / LANES_PER_ROW, ch = lane % LANES_PER_ROW;
-            vdat[p] = *reinterpret_cast<const u32x4*>(stage + row * C::EPI_STRIDE + ch * 16);
-        }
-#pragma unroll
-        for (int p = 0; p < BATCH; ++p) {
-            const int row = (p0 + p) * ROWS_PER_PASS + lane / LANES_PER_ROW, ch = lane % LANES_PER_ROW;
-            // non-temporal: the output is not read again by this launch, and a workgroup cannot retire
-            // before its stores are acknowledged
-            __builtin_nontemporal_store(vdat[p], reinterpret_cast<u32x4*>(Cw + (int64_t)row * g.ldc + ch * 8));
-        }
+        finish(IC<EPI_NONE>{});
     }
 }
 

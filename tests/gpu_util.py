@@ -10,15 +10,15 @@ import paper_2305_13525_amd as axo
 REL_FRO_TOL = 2e-3      # relative Frobenius error against the fp64 oracle
 PER_ELEM_TOL = 1e-2     # |C - O| <= 1e-2 * max_c |O[r, c]|
 # The 2e-3 Frobenius bound is a statement about the RMS of round-to-nearest-even bf16 rounding
-# (about 1.66e-3 of the value) and only holds once enough elements average out.  A single
-# correctly rounded element can be off by the unit roundoff 2^-8 = 3.9e-3, so outputs with
-# fewer than SMALL_OUTPUT elements are held to that hard bound (plus 2^-12 for fp32 summation).
+# (about 1.66e-3 of the value) and only holds once enough elements average out: a single
+# correctly rounded element can be off by the unit roundoff 2^-8 = 3.9e-3.  It is therefore
+# applied to outputs of at least SMALL_OUTPUT elements.  The statement that holds at any size, and
+# is applied at every size, is the element-wise one: every output is within ONE bf16 step of the
+# oracle value rounded once to bf16, unless it is so close to zero that the fp32 accumulation error
+# (FAR_ABS of the row's largest magnitude: the benchmark's sums of up to 16384 products carry about
+# 1e-5 of it) spans more than a bf16 step there.
 SMALL_OUTPUT = 4096
-SMALL_FRO_TOL = 2.0 ** -8 + 2.0 ** -12
-
-
-def fro_tol(n_elems: int) -> float:
-    return REL_FRO_TOL if n_elems >= SMALL_OUTPUT else SMALL_FRO_TOL
+FAR_ABS = 1e-4
 
 
 def to_dev(bits: np.ndarray) -> torch.Tensor:
@@ -84,8 +84,16 @@ def trio(p, Xb, Wb, dYb, bias_b=None, epilogue=0):
 
 
 def assert_close(oracle_mod, cand_bits, ref, what="", fro=None, per_elem=PER_ELEM_TOL):
-    r = oracle_mod.compare_bf16(np.ascontiguousarray(cand_bits), ref, per_elem)
+    cand_bits = np.ascontiguousarray(cand_bits)
+    r = oracle_mod.compare_bf16(cand_bits, ref, per_elem)
     assert r["n_nonfinite"] == 0, (what, r)
-    assert r["rel_fro"] <= (fro_tol(ref.size) if fro is None else fro), (what, r)
+    steps = oracle_mod.ulp_distance_bf16(cand_bits, ref)
+    err = np.abs((cand_bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64) - ref)
+    row_max = np.max(np.abs(ref), axis=1, keepdims=True) if ref.size else np.zeros((ref.shape[0], 1))
+    r["n_beyond_1_step"] = int(np.count_nonzero(steps > 1))          # reported
+    r["n_far"] = int(np.count_nonzero((steps > 1) & (err > FAR_ABS * row_max)))   # gated
+    assert r["n_far"] == 0, (what, r)
+    if fro is not None or ref.size >= SMALL_OUTPUT:
+        assert r["rel_fro"] <= (REL_FRO_TOL if fro is None else fro), (what, r)
     assert r["n_bad"] == 0, (what, r)
     return r

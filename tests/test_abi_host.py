@@ -108,6 +108,7 @@ def test_shard_dims_errors():
 # The pointer checks below never reach a HIP call: every call is malformed on purpose, so the
 # fake addresses are never dereferenced.
 A = 0x10000  # 16-byte aligned fake device address
+A1, A2, A3, A4, A5, A6, A7 = (A + i * 0x100000 for i in range(1, 8))  # further ones, far enough apart for any matrix here
 
 
 def test_fwd_argument_errors():
@@ -133,6 +134,59 @@ def test_dgrad_wgrad_argument_errors():
     assert w(X=None) == NULL_PTR and w(dY=None) == NULL_PTR and w(dW=None) == NULL_PTR
     assert w(ldx=16) == BAD_LD and w(lddw=40) == BAD_LD and w(dW=A + 4) == MISALIGNED
     assert d(p=None) == NULL_PTR and w(p=None) == NULL_PTR
+
+
+def test_output_must_not_share_bytes_with_an_input():
+    """The header's rule, enforced on the host: the kernels write output tiles while other workgroups
+    still read the operands (and compute the overlap of a ragged output's tiles twice), so a product
+    written over one of its own inputs is refused.  Sharing a buffer without sharing bytes is fine."""
+    M, K, N = 64, 32, 48
+    p = axo.Problem.make((1, 1, 1), (0, 0, 0), M, K, N)
+    fwd = lambda X, ldx, Y, ldy: axo.axo_fc_fwd(p, X, ldx, A1, N, None, 0, Y, ldy, check=False)
+    # the route query plans a product without launching it; here the planners' verdict is all we want,
+    # so every call below is made on a problem with nothing to launch where it would pass
+    none = axo.Problem.make((1, 1, 1), (0, 0, 0), M, K, 0)
+    assert axo.axo_fc_fwd(none, A, K, A1, 8, None, 0, A, 8, check=False) == OK      # no output element: no overlap
+    assert fwd(A, K, A, N) == BAD_ARG                                               # Y over X
+    assert fwd(A, K, A + (M - 1) * K * 2 + K * 2 - 16, N) == BAD_ARG                # Y begins on X's last 16 bytes
+    assert axo.axo_fc_dgrad(p, A, N, A1, N, A1 + 64, K, check=False) == BAD_ARG      # dX inside W
+    assert axo.axo_fc_wgrad(p, A, K, A1, N, A1, N, check=False) == BAD_ARG           # dW over dY
+    # X and Y as interleaved column blocks of one buffer with rows of K + N elements share no byte:
+    # that call passes validation (and would go on to launch, so it is asked as a route here)
+    levels = axo.axo_layer_step_levels(
+        [axo.Layer(p, 0, 0, A, K + N, A1, N, None, A + K * 2, K + N, A3, N, A4, K, A5, N)], check=False)
+    assert levels[0] == OK
+    # ... while shifting Y one 16-byte step to the left runs it into X's columns
+    levels = axo.axo_layer_step_levels(
+        [axo.Layer(p, 0, 0, A, K + N, A1, N, None, A + K * 2 - 16, K + N, A3, N, A4, K, A5, N)], check=False)
+    assert levels[0] == BAD_ARG
+
+
+def test_routes_follow_shape_and_leading_dimensions():
+    """axo_fc_route: which kernels a product takes is decided on the host from the shard shape and the
+    leading dimensions.  The tuned kernel forms 32-bit byte offsets inside an operand tile, so the span
+    it walks must stay below 4 GiB; for wgrad that span is the token count ROUNDED UP to 128."""
+    mk = lambda M, K, N: axo.Problem.make((1, 1, 1), (0, 0, 0), M, K, N)
+    route = lambda p, op, a, b, c: axo.axo_fc_route(p, op, a, b, c)[1]
+    FWD, DG, WG = axo.AXO_OP_FWD, axo.AXO_OP_DGRAD, axo.AXO_OP_WGRAD
+    p = mk(4096, 2048, 6144)                                    # benchmark config 2: all three tiled
+    assert [route(p, FWD, 2048, 6144, 6144), route(p, DG, 6144, 6144, 2048), route(p, WG, 2048, 6144, 6144)] == [1, 1, 1]
+    assert route(mk(0, 32, 48), FWD, 32, 48, 48) == axo.AXO_ROUTE_NONE
+    assert route(mk(77, 40, 24), FWD, 40, 24, 24) == axo.AXO_ROUTE_GENERAL
+    assert route(mk(520, 384, 264), FWD, 384, 264, 264) == axo.AXO_ROUTE_COVERED
+    assert route(mk(520, 264, 384), WG, 264, 384, 384) == axo.AXO_ROUTE_COVERED
+    assert route(mk(1000, 256, 384), WG, 256, 384, 384) == axo.AXO_ROUTE_TILED       # any token count
+    # 450 tokens, 4.3 M elements apart: 450 rows span 3.87 GB, the 512 walked rows 4.4 GB
+    assert route(mk(450, 256, 384), WG, 4_300_000, 4_300_000, 384) == axo.AXO_ROUTE_GENERAL
+    assert route(mk(384, 256, 384), WG, 4_300_000, 4_300_000, 384) == axo.AXO_ROUTE_TILED    # 384 = 3 * 128 rows: 3.3 GB
+    # 131005 tokens 16392 elements apart: the valid rows end just below the limit, row 131071 does not
+    assert (131005 * 16392 + 256) * 2 < 0xFFFF0000 < (131072 * 16392 + 256) * 2
+    assert route(mk(131005, 256, 384), WG, 16392, 16392, 384) == axo.AXO_ROUTE_GENERAL
+    assert route(mk(130944, 256, 384), WG, 16392, 16392, 384) == axo.AXO_ROUTE_TILED
+    # errors are those of the product's own argument checks
+    assert axo.axo_fc_route(mk(64, 32, 48), FWD, 24, 48, 48, check=False)[0] == BAD_LD
+    assert axo.axo_fc_route(mk(64, 32, 48), 5, 32, 48, 48, check=False)[0] == BAD_ARG
+    assert axo.library().axo_fc_route(None, 0, 8, 8, 8, None) == NULL_PTR
 
 
 def test_workspace_query():
@@ -161,14 +215,18 @@ def test_layer_step_validates_whole_chain_first(entry):
     # T == 0 and N == 0: none of the three products has an output element, so nothing launches
     good = axo.Layer(axo.Problem.make((1, 1, 1), (0, 0, 0), 0, 32, 0), 0, 0, A, 32, A, 8, None, A, 8, A, 8,
                      A, 32, A, 8)
-    bad = axo.Layer(axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 48), 0, 0, A, 32, A, 48, None, A, 48, A, 48,
-                    None, 32, A, 48)  # dX missing
+    bad = axo.Layer(axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 48), 0, 0, A, 32, A1, 48, None, A2, 48, A3, 48,
+                    None, 32, A5, 48)  # dX missing
     assert step([], check=False) == OK
     assert step([good], check=False) == OK  # empty shard: no launch
     assert step([good, bad], check=False) == NULL_PTR
     worse = axo.Layer(axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 48), 9, 0, A, 32, A, 48, None, A, 48, A, 48,
                       A, 32, A, 48)
     assert step([worse], check=False) == BAD_EPI
+    # an output that shares bytes with an input of its own product is refused (here dX over dY)
+    alias = axo.Layer(axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 48), 0, 0, A, 32, A1, 48, None, A2, 48, A3, 48,
+                      A3, 32, A5, 48)
+    assert step([good, alias], check=False) == BAD_ARG
     assert getattr(axo.library(), entry)(None, 2, None, 0, None) == NULL_PTR
     assert getattr(axo.library(), entry)(None, -1, None, 0, None) == BAD_ARG
     assert axo.axo_layer_step_workspace_bytes([good, bad]) >= 0
@@ -211,11 +269,14 @@ def test_dependence_levels_are_decided_on_byte_ranges():
     # write after read: layer one's Y is the buffer layer zero's forward reads as X; fwd 1 waits for
     # fwd 0, and wgrad 0, which in program order reads that buffer after fwd 1 has rewritten it, for fwd 1
     assert levels([l0, layer(a[6], a[7], a[0], a[9], a[10], a[11])]) == [0, 1, 0, 0, 0, 2]
-    # an output that begins on the last 16 bytes of an input: X spans (M - 1) * K + K elements;
-    # fwd writes into what it reads (its own level is 0; wgrad, which reads X, comes after it)
+    # an output that begins on the last 16 bytes of one of its own inputs is refused; one that
+    # begins right behind it is fine.  X spans (M - 1) * K + K elements
     x_bytes = ((M - 1) * K + K) * 2
-    assert levels([layer(a[0], a[1], a[0] + x_bytes - 16, a[3], a[4], a[5])]) == [0, 0, 1]
+    assert axo.axo_layer_step_levels([layer(a[0], a[1], a[0] + x_bytes - 16, a[3], a[4], a[5])], check=False)[0] == BAD_ARG
     assert levels([layer(a[0], a[1], a[0] + x_bytes, a[3], a[4], a[5])]) == [0, 0, 0]
+    # the same 16 bytes shared with an input of ANOTHER product are a dependence, not an error:
+    # layer one's Y ends on the first bytes of layer zero's X, which wgrad 0 reads afterwards
+    assert levels([l0, layer(a[6], a[7], a[0] - ((M - 1) * N + N) * 2 + 16, a[9], a[10], a[11])]) == [0, 1, 0, 0, 0, 2]
     # column blocks interleaved in one buffer (ld twice the row length) count as overlapping
     assert levels([layer(a[0], a[1], a[2], a[3], a[4], a[5], ldy=2 * N),
                    layer(a[6], a[7], a[2] + 2 * N, a[9], a[10], a[11], ldy=2 * N)]) == [0, 1, 0, 0, 0, 0]
@@ -244,21 +305,25 @@ def test_missing_library_fails_loudly(monkeypatch):
 def test_backward_extras_argument_errors():
     p = axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 48)
     # dgrad through an activation: act must name one of the two GELUs; pre is a [M x Kl] matrix
-    assert axo.axo_fc_dgrad_act(p, A, 48, A, 48, A, 32, 1, A, 32, check=False) == BAD_EPI
-    assert axo.axo_fc_dgrad_act(p, A, 48, A, 48, None, 32, 2, A, 32, check=False) == NULL_PTR
-    assert axo.axo_fc_dgrad_act(p, A, 48, A, 48, A, 24, 3, A, 32, check=False) == BAD_LD
-    assert axo.axo_fc_dgrad_act(p, A, 40, A, 48, A, 32, 2, A, 32, check=False) == BAD_LD
+    assert axo.axo_fc_dgrad_act(p, A, 48, A1, 48, A2, 32, 1, A3, 32, check=False) == BAD_EPI
+    assert axo.axo_fc_dgrad_act(p, A, 48, A1, 48, None, 32, 2, A3, 32, check=False) == NULL_PTR
+    assert axo.axo_fc_dgrad_act(p, A, 48, A1, 48, A2, 24, 3, A3, 32, check=False) == BAD_LD
+    assert axo.axo_fc_dgrad_act(p, A, 40, A1, 48, A2, 32, 2, A3, 32, check=False) == BAD_LD
+    assert axo.axo_fc_dgrad_act(p, A, 48, A1, 48, A2, 32, 2, A2, 32, check=False) == BAD_ARG   # dX over pre
     # fp32 accumulation: ld in floats, multiple of 4, 16-byte aligned base
-    assert axo.axo_fc_wgrad_acc(p, A, 32, A, 48, None, 48, check=False) == NULL_PTR
-    assert axo.axo_fc_wgrad_acc(p, A, 32, A, 48, A, 40, check=False) == BAD_LD
-    assert axo.axo_fc_wgrad_acc(p, A, 32, A, 48, A, 50, check=False) == MISALIGNED
-    assert axo.axo_fc_wgrad_acc(p, A, 32, A, 48, A + 8, 48, check=False) == MISALIGNED
-    assert axo.axo_fc_wgrad_acc(p, A, 24, A, 48, A, 48, check=False) == BAD_LD
+    assert axo.axo_fc_wgrad_acc(p, A, 32, A1, 48, None, 48, check=False) == NULL_PTR
+    assert axo.axo_fc_wgrad_acc(p, A, 32, A1, 48, A2, 40, check=False) == BAD_LD
+    assert axo.axo_fc_wgrad_acc(p, A, 32, A1, 48, A2, 50, check=False) == MISALIGNED
+    assert axo.axo_fc_wgrad_acc(p, A, 32, A1, 48, A2 + 8, 48, check=False) == MISALIGNED
+    assert axo.axo_fc_wgrad_acc(p, A, 24, A1, 48, A2, 48, check=False) == BAD_LD
+    # the fp32 matrix is twice as large in bytes as the bf16 stand-in: its tail reaching into X is caught
+    assert axo.axo_fc_wgrad_acc(p, A, 32, A1, 48, A - 32 * 48 * 4 + 16, 48, check=False) == BAD_ARG
     # bias gradient
     assert axo.axo_bias_grad(p, A, 48, None, 0, check=False) == NULL_PTR
-    assert axo.axo_bias_grad(p, A, 48, A + 2, 0, check=False) == MISALIGNED
-    assert axo.axo_bias_grad(p, A, 48, A, 2, check=False) == BAD_ARG
-    assert axo.axo_bias_grad(p, A, 40, A, 0, check=False) == BAD_LD
+    assert axo.axo_bias_grad(p, A, 48, A1 + 2, 0, check=False) == MISALIGNED
+    assert axo.axo_bias_grad(p, A, 48, A1, 2, check=False) == BAD_ARG
+    assert axo.axo_bias_grad(p, A, 40, A1, 0, check=False) == BAD_LD
+    assert axo.axo_bias_grad(p, A, 48, A + 96, 0, check=False) == BAD_ARG                      # db inside dY
     # nothing to do: valid without a device
     pn = axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 0)
     assert axo.axo_bias_grad(pn, A, 8, A, 0, check=False) == OK
@@ -281,19 +346,22 @@ def test_bench_refuses_more_than_one_gpu():
 def test_layer_step_ext_validation():
     """The extras of axo_layer_step_ext are validated like the single calls, before any launch."""
     p = axo.Problem.make((1, 1, 1), (0, 0, 0), 64, 32, 48)
-    base = axo.Layer(p, 0, 0, A, 32, A, 48, None, A, 48, A, 48, A, 32, A, 48)
+    base = axo.Layer(p, 0, 0, A, 32, A1, 48, None, A2, 48, A3, 48, A4, 32, A5, 48)
     ext = axo.LayerExt.make
     step = lambda ls: axo.axo_layer_step_ext(ls, check=False)
     assert step([]) == OK
     assert step([ext(base, act_below=2)]) == BAD_EPI                        # an activation without its pre-activation
-    assert step([ext(base, pre=A, ldpre=32, act_below=0)]) == BAD_EPI       # a pre-activation without an activation
-    assert step([ext(base, pre=A, ldpre=32, act_below=1)]) == BAD_EPI       # bias alone is no activation
-    assert step([ext(base, pre=A, ldpre=24, act_below=2)]) == BAD_LD
-    assert step([ext(base, dW32=A, lddw32=40)]) == BAD_LD
-    assert step([ext(base, dW32=A, lddw32=50)]) == MISALIGNED
-    assert step([ext(base, db=A + 2)]) == MISALIGNED
-    assert step([ext(base, db=A, accumulate_db=2)]) == BAD_ARG
-    no_dw = axo.Layer(p, 0, 0, A, 32, A, 48, None, A, 48, A, 48, A, 32, None, 48)
+    assert step([ext(base, pre=A6, ldpre=32, act_below=0)]) == BAD_EPI      # a pre-activation without an activation
+    assert step([ext(base, pre=A6, ldpre=32, act_below=1)]) == BAD_EPI      # bias alone is no activation
+    assert step([ext(base, pre=A6, ldpre=24, act_below=2)]) == BAD_LD
+    assert step([ext(base, pre=A4, ldpre=32, act_below=2)]) == BAD_ARG      # dX written over the pre-activation it reads
+    assert step([ext(base, dW32=A7, lddw32=40)]) == BAD_LD
+    assert step([ext(base, dW32=A7, lddw32=50)]) == MISALIGNED
+    assert step([ext(base, dW32=A3, lddw32=48)]) == BAD_ARG                 # the fp32 gradient over dY
+    assert step([ext(base, db=A7 + 2)]) == MISALIGNED
+    assert step([ext(base, db=A7, accumulate_db=2)]) == BAD_ARG
+    assert step([ext(base, db=A3 + 64)]) == BAD_ARG                         # the bias gradient inside dY
+    no_dw = axo.Layer(p, 0, 0, A, 32, A1, 48, None, A2, 48, A3, 48, A4, 32, None, 48)
     assert step([ext(no_dw)]) == NULL_PTR                                    # plain wgrad needs layer.dW ...
     empty = axo.Problem.make((1, 1, 1), (0, 0, 0), 0, 32, 0)                # (nothing to launch: valid anywhere)
     nothing = axo.Layer(empty, 0, 0, A, 32, A, 8, None, A, 8, A, 8, A, 32, None, 8)
@@ -333,9 +401,14 @@ def test_dependence_levels_on_random_chains():
         # half-slot offsets make partial overlaps as well as exact aliases
         pick = lambda: rnd.choice(pool) + rnd.choice((0, 0, 0, 1 << 11))
         lays = []
-        for _ in range(n):
-            X, W, Y, dY, dX, dW = (pick() for _ in range(6))
-            lays.append((X, W, Y, dY, dX, dW))
+        ov = lambda r, q: r[0] < q[1] and q[0] < r[1]
+        while len(lays) < n:
+            lay = tuple(pick() for _ in range(6))
+            # an output that shares bytes with an input of its own product is refused by the library
+            # (all matrices here are contiguous, so sharing bytes is the same as overlapping ranges)
+            if any(ov(out, r) for ins, out in products(lay) for r in ins):
+                continue
+            lays.append(lay)
         layers = [axo.Layer(p, 0, 0, X, K, W, N, None, Y, N, dY, N, dX, K, dW, N) for X, W, Y, dY, dX, dW in lays]
         rc, n_levels, lv = axo.axo_layer_step_levels(layers)
         assert rc == OK and len(lv) == 3 * n

@@ -34,6 +34,40 @@ def test_dgrad_through_gelu(M, Kl, Nl, act):
     gu.assert_close(oracle, gu.to_host(dX), oracle.fc_dgrad_act(dYb, Wb, Pb, act), f"dgrad_act {act}")
 
 
+@pytest.mark.parametrize("act", [0, axo.AXO_EPI_BIAS_GELU_TANH, axo.AXO_EPI_BIAS_GELU_ERF])
+@pytest.mark.parametrize("M,Kl,Nl", [(512, 512, 512),    # 256x256 tiles only
+                                     (512, 128, 256),    # 256x128 tiles only
+                                     (512, 640, 384)])   # both tile sizes in one launch
+def test_dgrad_epilogues_by_position(M, Kl, Nl, act):
+    """Every dgrad epilogue kind on both tile sizes, bit for bit and by position.  W holds one 1 per row
+    (W[k, k % Nl] = 1), so dY . W^T puts dY[t, k % Nl] at [t, k] exactly; dY holds small integers that
+    encode their position; the pre-activations are 0, +20 or -20, where both GELU derivatives are
+    exactly 1/2, 1 and 0.  An output element that lands in the wrong place, or takes its factor from the
+    wrong place, differs in its bits."""
+    rng = np.random.default_rng(5)
+    t, n = np.meshgrid(np.arange(M), np.arange(Nl), indexing="ij")
+    dYv = ((t * 7 + n * 3) % 253 - 126).astype(np.float32)          # integers in [-126, 126]: exact in bf16
+    Wv = np.zeros((Kl, Nl), dtype=np.float32)
+    Wv[np.arange(Kl), np.arange(Kl) % Nl] = 1.0
+    sel = rng.integers(0, 3, size=(M, Kl))
+    prev = np.choose(sel, [0.0, 20.0, -20.0]).astype(np.float32)
+    factor = np.choose(sel, [0.5, 1.0, 0.0]).astype(np.float32)
+    dYb, Wb, Pb = syn.f32_to_bf16_bits(dYv), syn.f32_to_bf16_bits(Wv), syn.f32_to_bf16_bits(prev)
+    want = dYv[:, np.arange(Kl) % Nl] * (factor if act else 1.0)    # halves of integers <= 126: exact in bf16
+    dY, W, pre, dX = gu.to_dev(dYb), gu.to_dev(Wb), gu.to_dev(Pb), gu.empty_dev(M, Kl)
+    if act:
+        axo.axo_fc_dgrad_act(P(M, Kl, Nl), dY.data_ptr(), Nl, W.data_ptr(), Nl, pre.data_ptr(), Kl, act, dX.data_ptr(), Kl,
+                             None, 0, gu.stream())
+    else:
+        axo.axo_fc_dgrad(P(M, Kl, Nl), dY.data_ptr(), Nl, W.data_ptr(), Nl, dX.data_ptr(), Kl, None, 0, gu.stream())
+    torch.cuda.synchronize()
+    got = syn.bf16_bits_to_f64(gu.to_host(dX))
+    assert np.array_equal(got, want.astype(np.float64)), np.argwhere(got != want)[:5]   # -0 == 0 counts as equal
+    # the oracle agrees with the construction (so the expectation is not this test's own invention)
+    ref = oracle.fc_dgrad_act(dYb, Wb, Pb, act) if act else oracle.fc_dgrad(dYb, Wb)
+    assert np.max(np.abs(ref - want)) <= 1e-12 * 126
+
+
 def test_dgrad_through_gelu_in_place_shard():
     """Shard of a (2,2,2) grid addressed inside the global tensors (leading dimensions > row length)."""
     T, K, N, grid, c = 512, 512, 1024, (2, 2, 2), (1, 0, 1)

@@ -230,3 +230,55 @@ def test_bf16_rounding_is_nearest_even():
     f = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 2 ** -8 + 2 ** -20, 1.0 + 3 * 2 ** -8, -(1.0 + 2 ** -8)], dtype=np.float32)
     got = syn.f32_to_bf16_bits(f)
     assert list(got) == [0x3F80, 0x3F80, 0x3F81, 0x3F82, 0xBF80]
+
+
+def test_single_rounding_to_bf16_against_exact_rationals():
+    """oracle.rne_bf16_bits against a brute-force search in exact rational arithmetic: of the two bf16
+    neighbours of x the nearer one, the even one on a tie.  Values chosen to sit on and next to ties,
+    where a double rounding through fp32 goes wrong."""
+    from fractions import Fraction
+
+    def bf16_value(bits):
+        return Fraction(float(np.array([bits], dtype=np.uint16).astype(np.uint32).__lshift__(16).view(np.float32)[0]))
+
+    def brute(x):
+        fx = Fraction(x)
+        neg = fx < 0
+        mag = -fx if neg else fx
+        lo, hi = 0, 0x7F7F                      # largest bf16 magnitude not above mag, by bisection on the bits
+        while lo < hi:
+            mid = (lo + hi + 1) // 2
+            if bf16_value(mid) <= mag:
+                lo = mid
+            else:
+                hi = mid - 1
+        below, above = bf16_value(lo), bf16_value(lo + 1)
+        if mag - below < above - mag:
+            pick = lo
+        elif mag - below > above - mag:
+            pick = lo + 1
+        else:
+            pick = lo if lo % 2 == 0 else lo + 1
+        return pick | (0x8000 if neg and pick != 0 else 0) if pick != 0 else (0x8000 if neg else 0)
+
+    rng = np.random.default_rng(11)
+    xs = list(rng.standard_normal(200) * 10.0 ** rng.integers(-6, 6, 200))
+    for base in (1.0, 1.5, 3.0, 0.0078125, 1000.0):
+        ulp = 2.0 ** (np.floor(np.log2(base)) - 7)
+        for k in (0, 1, 2, 3):
+            tie = base + (k + 0.5) * ulp          # exactly between two bf16 values
+            xs += [tie, -tie, np.nextafter(tie, 0.0), np.nextafter(tie, 1e9),
+                   tie + ulp * 2.0 ** -30, tie - ulp * 2.0 ** -30]   # lost when rounding to fp32 first
+    xs = np.array(xs, dtype=np.float64)
+    got = oracle.rne_bf16_bits(xs)
+    want = np.array([brute(float(x)) for x in xs], dtype=np.uint16)
+    assert np.array_equal(got, want), np.argwhere(got != want)[:5]
+
+
+def test_ulp_distance_counts_bf16_steps():
+    ref = np.array([1.0, 1.0, 1.0, -2.0, 0.0, 0.0, 3.14159, 1e-3], dtype=np.float64)
+    one, nxt, prv = 0x3F80, 0x3F81, 0x3F7F
+    cand = np.array([one, nxt, prv, 0xC001, 0x8000, 0x0001, 0x4049, 0x3A83], dtype=np.uint16)
+    # 1.0 exact / one up / one down (across the binade); -2.0 one step away; -0 equals +0; the
+    # smallest denormal is one step from zero; pi rounds to 0x4049; 1e-3 rounds to 0x3A83
+    assert list(oracle.ulp_distance_bf16(cand, ref)) == [0, 1, 1, 1, 0, 1, 0, 0]

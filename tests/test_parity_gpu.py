@@ -380,6 +380,31 @@ def test_very_large_leading_dimensions(ld_elems, what):
     torch.cuda.empty_cache()
 
 
+def test_wgrad_ragged_token_count_with_a_very_large_leading_dimension():
+    """wgrad walks its token count rounded up to 128.  With 450 tokens 4.3 M elements apart the 450
+    rows span 3.87 GB (below the tuned kernel's 4 GiB limit) but the 512 rows the kernel would walk do
+    not: the library has to send the product to the general kernel."""
+    M, Kl, Nl, ld_elems = 450, 256, 384, 4_300_000
+    Xb, _, dYb = rand_trio(M, Kl, Nl, 971)
+    p = P(M, Kl, Nl)
+    assert axo.axo_fc_route(p, axo.AXO_OP_WGRAD, ld_elems, ld_elems, Nl)[1] == axo.AXO_ROUTE_GENERAL
+    held = []
+
+    def wide(bits):
+        big = torch.empty((bits.shape[0], ld_elems), dtype=torch.int16, device="cuda:0")
+        held.append(big)
+        view = big[:, :bits.shape[1]]
+        view.copy_(gu.to_dev(bits))
+        return view
+
+    X, dY, dW = wide(Xb), wide(dYb), gu.empty_dev(Kl, Nl)
+    keep = gu.run_wgrad(p, X, dY, dW)
+    torch.cuda.synchronize()
+    gu.assert_close(oracle, gu.to_host(dW), oracle.fc_wgrad(Xb, dYb), "wgrad, 450 tokens 4.3 M elements apart")
+    del keep, held, X, dY
+    torch.cuda.empty_cache()
+
+
 def test_concurrent_host_threads_on_their_own_streams():
     """Four host threads enqueue products of different shapes on their own streams at the same time
     (ctypes releases the interpreter lock during a call, so the library's planners and their
@@ -450,6 +475,70 @@ def test_denormals_infinities_and_nans():
     assert inf_cols.sum() == Nl - 1
     assert np.array_equal(np.isinf(gotf[2]), inf_cols) and np.array_equal(np.sign(gotf[2][inf_cols]), np.sign(ref[2][inf_cols]))
     assert np.isnan(ref[3]).all() and np.isnan(gotf[3]).all()
+
+
+def check_value_classes(got_bits, ref, special_rows, what):
+    """NaNs where the oracle has NaNs, infinities of the same sign where it has infinities, and the
+    rows without special values within the usual tolerances."""
+    gotf = syn.bf16_bits_to_f64(got_bits)
+    assert np.array_equal(np.isnan(gotf), np.isnan(ref)), what
+    assert np.array_equal(np.isinf(gotf), np.isinf(ref)), what
+    inf = np.isinf(ref)
+    assert np.array_equal(np.sign(gotf[inf]), np.sign(ref[inf])), what
+    plain = np.array([r for r in range(ref.shape[0]) if r not in special_rows])
+    assert np.isfinite(ref[plain]).all()
+    gu.assert_close(oracle, got_bits[plain], ref[plain], what)
+
+
+def test_special_values_in_wgrad_with_a_ragged_token_count():
+    """wgrad on the tuned kernel with a token count that is no multiple of 128: the kernel walks 1024
+    rows of X and dY and must read rows 1000..1023 as zeros.  Here those rows EXIST in memory (the
+    operands are the first 1000 rows of larger buffers) and hold NaNs, so a surplus row that leaked in
+    would poison every output; an infinity sits in the last valid row, a NaN elsewhere."""
+    M, Kl, Nl = 1000, 256, 384
+    Xb, _, dYb = rand_trio(M, Kl, Nl, 991)
+    Xb, dYb = Xb.copy(), dYb.copy()
+    Xb[999, 5] = 0x7F80         # +inf in the last token: row 5 of dW becomes +-inf ...
+    dYb[999, 17] = 0x0000       # ... and NaN where it meets a zero
+    Xb[10, 7] = 0x7FC0          # NaN: row 7 of dW is NaN
+    dYb[500, 40] = 0xFF80       # -inf in dY: column 40 of dW is +-inf (NaN in rows 5 and 7)
+    Xfull = np.full((1024, Kl), 0x7FC0, dtype=np.uint16)
+    dYfull = np.full((1024, Nl), 0x7FC0, dtype=np.uint16)
+    Xfull[:M], dYfull[:M] = Xb, dYb
+    X, dY, dW = gu.to_dev(Xfull), gu.to_dev(dYfull), gu.empty_dev(Kl, Nl)
+    p = P(M, Kl, Nl)
+    assert axo.axo_fc_route(p, axo.AXO_OP_WGRAD, Kl, Nl, Nl)[1] == axo.AXO_ROUTE_TILED
+    keep = gu.run_wgrad(p, X, dY, dW)
+    torch.cuda.synchronize()
+    del keep
+    with np.errstate(invalid="ignore", over="ignore"):
+        ref = oracle.fc_wgrad(Xb, dYb)
+    assert np.isnan(ref[7]).all() and np.isnan(ref[5, 17]) and np.isinf(ref[0, 40])
+    got = gu.to_host(dW)
+    cols = np.array([c for c in range(Nl) if c != 40])          # column 40 is special in every row
+    check_value_classes(got[:, cols], ref[:, cols], (5, 7), "wgrad, ragged token count")
+    check_value_classes(got[:, 40:41], ref[:, 40:41], range(Kl), "wgrad, ragged token count, column 40")
+
+
+def test_special_values_in_an_output_covered_with_overlapping_tiles():
+    """A forward product whose ragged output is covered with whole tiles that overlap: elements in the
+    overlap are computed twice and must come out the same, special values included."""
+    M, Kl, Nl = 520, 384, 264
+    Xb, Wb, _ = rand_trio(M, Kl, Nl, 992)
+    Xb, Wb = Xb.copy(), Wb.copy()
+    Xb[519, 3] = 0x7F80         # +inf in the last row (inside the band of the last 256 rows only)
+    Wb[3, 263] = 0x0000         # times zero in the last column (inside the band of the last 128 columns only)
+    Xb[300, 9] = 0x7FC0         # NaN in a row that interior and row band both cover
+    X, W, Y = gu.to_dev(Xb), gu.to_dev(Wb), gu.empty_dev(M, Nl)
+    p = P(M, Kl, Nl)
+    assert axo.axo_fc_route(p, axo.AXO_OP_FWD, Kl, Nl, Nl)[1] == axo.AXO_ROUTE_COVERED
+    keep = gu.run_fwd(p, X, W, Y)
+    torch.cuda.synchronize()
+    del keep
+    with np.errstate(invalid="ignore", over="ignore"):
+        ref = oracle.fc_fwd(Xb, Wb)
+    assert np.isnan(ref[519, 263]) and np.isnan(ref[300]).all()
+    check_value_classes(gu.to_host(Y), ref, (300, 519), "covered forward")
 
 
 def test_scheduled_step_equals_ordered_step_on_random_dependent_chains():
