@@ -83,7 +83,11 @@ def trio(p, Xb, Wb, dYb, bias_b=None, epilogue=0):
     return to_host(Y), to_host(dX), to_host(dW)
 
 
-def assert_close(oracle_mod, cand_bits, ref, what="", fro=None, per_elem=PER_ELEM_TOL):
+def assert_close(oracle_mod, cand_bits, ref, what="", fro=None, per_elem=PER_ELEM_TOL, one_step=None):
+    """`fro` overrides the Frobenius bound for results that went through more than one rounding (sums of
+    bf16 partial results); the one-step gate is for singly rounded results and is then off by default."""
+    if one_step is None:
+        one_step = fro is None
     cand_bits = np.ascontiguousarray(cand_bits)
     r = oracle_mod.compare_bf16(cand_bits, ref, per_elem)
     assert r["n_nonfinite"] == 0, (what, r)
@@ -92,7 +96,7 @@ def assert_close(oracle_mod, cand_bits, ref, what="", fro=None, per_elem=PER_ELE
     row_max = np.max(np.abs(ref), axis=1, keepdims=True) if ref.size else np.zeros((ref.shape[0], 1))
     r["n_beyond_1_step"] = int(np.count_nonzero(steps > 1))          # reported
     r["n_far"] = int(np.count_nonzero((steps > 1) & (err > FAR_ABS * row_max)))   # gated
-    assert r["n_far"] == 0, (what, r)
+    assert r["n_far"] == 0 or not one_step, (what, r)
     if fro is not None or ref.size >= SMALL_OUTPUT:
         assert r["rel_fro"] <= (REL_FRO_TOL if fro is None else fro), (what, r)
     assert r["n_bad"] == 0, (what, r)

@@ -485,9 +485,10 @@ def check_value_classes(got_bits, ref, special_rows, what):
     assert np.array_equal(np.isinf(gotf), np.isinf(ref)), what
     inf = np.isinf(ref)
     assert np.array_equal(np.sign(gotf[inf]), np.sign(ref[inf])), what
-    plain = np.array([r for r in range(ref.shape[0]) if r not in special_rows])
-    assert np.isfinite(ref[plain]).all()
-    gu.assert_close(oracle, got_bits[plain], ref[plain], what)
+    plain = np.array([r for r in range(ref.shape[0]) if r not in special_rows], dtype=np.int64)
+    if plain.size:
+        assert np.isfinite(ref[plain]).all()
+        gu.assert_close(oracle, got_bits[plain], ref[plain], what)
 
 
 def test_special_values_in_wgrad_with_a_ragged_token_count():
