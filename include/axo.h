@@ -185,6 +185,26 @@ int axo_fc_wgrad_acc(const axo_problem_t *p, const void *X, int64_t ldx, const v
 int axo_bias_grad(const axo_problem_t *p, const void *dY, int64_t lddy, float *db, int accumulate,
                   void *hip_stream);
 
+/* Host only.  Bytes of device workspace axo_bias_grad_ws needs for this problem (0 for shards so
+ * small that it does not split their rows, and for an invalid problem). */
+size_t axo_bias_grad_workspace_bytes(const axo_problem_t *p);
+
+/* The bias gradient of axo_bias_grad, with the rows of dY split over several workgroups per
+ * 64-column strip: a 6144-column shard gives axo_bias_grad 96 workgroups for 256 compute units, which
+ * leaves it bound by memory latency; this form keeps about four workgroups per unit in flight.  Every
+ * workgroup writes the fp32 sums of its row slice to the workspace, and the one that finishes last
+ * adds the slices of its strip in ascending order: no floating-point atomics, so the result is a fixed
+ * function of the input (equal from run to run; it differs from axo_bias_grad's in the last bits,
+ * the rows being summed in another order).
+ * ws: device memory, 16-byte aligned, at least axo_bias_grad_workspace_bytes(p) bytes (may be NULL
+ * when that is 0).  It begins with one arrival counter per strip, which must be ZERO when the call
+ * starts executing and is zero again when it has finished: zero-fill the workspace once after
+ * allocating it and leave it to calls of this function.  Calls that share a workspace must not overlap
+ * in time (same stream, or ordered by events).
+ * Errors: those of axo_bias_grad; WORKSPACE (ws NULL or too small); MISALIGNED (ws). */
+int axo_bias_grad_ws(const axo_problem_t *p, const void *dY, int64_t lddy, float *db, int accumulate,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
 /* One FC layer of a chain: its problem, epilogue, and the caller's buffers with their leading
  * dimensions.  X and W are kept by the caller between forward and backward (the cache of
  * Algorithm 1's forward function).  dY is the gradient with respect to the layer's output

@@ -90,4 +90,120 @@ __global__ void __launch_bounds__(BG_THREADS) bias_grad_kernel(BiasGradArgs g) {
     bias_grad_strip<COLS, BG_THREADS>(g, blockIdx.x, part);
 }
 
+// ---- bias gradient with the rows split over workgroups ------------------------------------------
+// The strip kernel above gives a 6144-column shard 96 workgroups for 256 CUs and is bound by memory
+// latency (a third of the HBM rate).  Here a strip's rows are cut into S slices, one workgroup each
+// (S chosen by the host from the shape alone, for a few hundred workgroups in all; plain loads:
+// non-temporal ones were measured 5-10 % slower here);
+// a workgroup writes the fp32 sums of its slice to scratch memory [S x Nl], counts itself in on
+// its strip's arrival counter, and the workgroup that arrives last adds the S slices of the strip
+// in ascending slice order and writes db.  Which workgroup does that addition depends on timing,
+// what it computes does not: the result is a fixed function of the input (no floating-point
+// atomics).  No workgroup waits for another.
+//
+// Scratch: `counters` (one uint32 per strip) must be zero when the kernel starts; the last
+// workgroup of every strip sets its counter back to zero, so the kernel leaves them as it found
+// them.  `partial` needs no initialisation.  Launches that share scratch memory must not overlap.
+//
+// A 512-thread workgroup is 8 column lanes (16 bytes = 8 columns each: one 128-byte line per row)
+// by 64 row lanes; a thread's rows are 64 apart, their loads are issued eight at a time, summed in
+// ascending order; the 8 row lanes of a wave are combined with lane exchanges, the 8 waves through
+// LDS by wave 0, whose 64 lanes then own one column each.
+constexpr int BGS_THREADS = 512;
+constexpr int BGS_COLS = 64;
+constexpr int BGS_ROW_LANES = BGS_THREADS / (BGS_COLS / 8);  // 64
+constexpr int BGS_MAX_SPLIT = 32;
+
+struct BiasGradSplitArgs {
+    const bf16_t* dY; int64_t lddy;
+    float* db;
+    int M, Nl;
+    int accumulate;      // 0: db = sums, 1: db += sums
+    int S;               // row slices per strip (1: no scratch is touched)
+    int rows_per_slice;  // a multiple of BGS_ROW_LANES
+    float* partial;      // [S x Nl] fp32
+    uint32_t* counters;  // [number of strips]
+};
+
+__global__ void __launch_bounds__(BGS_THREADS) bias_grad_split_kernel(BiasGradSplitArgs g) {
+    __shared__ float part[BGS_THREADS / 64][BGS_COLS];
+    const int strip = blockIdx.x / g.S, slice = blockIdx.x % g.S;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cx = lane & 7, ry = wave * 8 + (lane >> 3);
+    const int col = strip * BGS_COLS + cx * 8;
+    const int valid = g.Nl - col;  // columns of this thread's chunk inside the matrix (may be <= 0 or >= 8)
+    const int row_end = min(g.M, (slice + 1) * g.rows_per_slice);
+    float s[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s[i] = 0.f;
+    if (valid >= 8) {
+        const bf16_t* base = g.dY + col;
+        int t = slice * g.rows_per_slice + ry;
+        for (; t + 7 * BGS_ROW_LANES < row_end; t += 8 * BGS_ROW_LANES) {  // eight loads in flight
+            u32x4 w[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                w[j] = *(reinterpret_cast<const u32x4*>(base + (int64_t)(t + j * BGS_ROW_LANES) * g.lddy));
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    s[2 * i] += __uint_as_float(w[j][i] << 16);
+                    s[2 * i + 1] += __uint_as_float(w[j][i] & 0xFFFF0000u);
+                }
+        }
+        for (; t < row_end; t += BGS_ROW_LANES) {
+            const u32x4 w = *(reinterpret_cast<const u32x4*>(base + (int64_t)t * g.lddy));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                s[2 * i] += __uint_as_float(w[i] << 16);
+                s[2 * i + 1] += __uint_as_float(w[i] & 0xFFFF0000u);
+            }
+        }
+    } else if (valid > 0) {  // ragged last chunk
+        for (int t = slice * g.rows_per_slice + ry; t < row_end; t += BGS_ROW_LANES)
+            for (int i = 0; i < valid; ++i) s[i] += bf16_bits_to_f32(g.dY[(int64_t)t * g.lddy + col + i]);
+    }
+    // the 8 row lanes of the wave (lane bits 3..5), in a fixed butterfly
+#pragma unroll
+    for (int m = 8; m < 64; m <<= 1)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s[i] += __shfl_xor(s[i], m, 64);
+    if (lane < 8) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) part[wave][cx * 8 + i] = s[i];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    // wave 0: lane c owns column strip * 64 + c
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < BGS_THREADS / 64; ++w) v += part[w][lane];
+    const int c = strip * BGS_COLS + lane;
+    if (g.S == 1) {
+        if (c < g.Nl) g.db[c] = g.accumulate ? g.db[c] + v : v;
+        return;
+    }
+    // Publication without cache-wide fences.  Slice sums, counter and the reads of the last
+    // workgroup are all device-scope atomic accesses: they go past the per-XCD L2 to the level all
+    // XCDs share.  Order: the wave's stores are complete (acknowledged at that level) before its
+    // lane 0 counts the slice in, and the last workgroup issues its reads only after the value of
+    // its own count has come back.  (A release / acquire fence pair does the same by writing back
+    // and invalidating the whole L2 per workgroup: measured three times slower than the strips.)
+    if (c < g.Nl) __hip_atomic_store(g.partial + (int64_t)slice * g.Nl + c, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    uint32_t arrived = 0;
+    if (lane == 0) arrived = __hip_atomic_fetch_add(g.counters + strip, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    arrived = __shfl(arrived, 0, 64);
+    if (arrived != (uint32_t)(g.S - 1)) return;
+    asm volatile("" ::: "memory");
+    if (c < g.Nl) {
+        float sum = 0.f;
+        for (int k = 0; k < g.S; ++k)
+            sum += __hip_atomic_load(g.partial + (int64_t)k * g.Nl + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        g.db[c] = g.accumulate ? g.db[c] + sum : sum;
+    }
+    if (lane == 0) __hip_atomic_store(g.counters + strip, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 }  // namespace axo

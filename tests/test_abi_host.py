@@ -332,6 +332,28 @@ def test_backward_extras_argument_errors():
     assert axo.axo_fc_dgrad_act(p0, A, 48, A, 48, A, 32, 2, A, 32, check=False) == OK
 
 
+def test_bias_grad_workspace_query_and_errors():
+    mk = lambda M, N: axo.Problem.make((1, 1, 1), (0, 0, 0), M, 8, N)
+    # 96 strips of 64 columns, 4 slices of 1024 rows (384 workgroups):
+    # 512 bytes of counters (96 * 4 rounded up to 256) + 4 * 6144 floats
+    assert axo.axo_bias_grad_workspace_bytes(mk(4096, 6144)) == 512 + 4 * 6144 * 4
+    assert axo.axo_bias_grad_workspace_bytes(mk(4096, 16384)) == 1024 + 2 * 16384 * 4
+    assert axo.axo_bias_grad_workspace_bytes(mk(77, 24)) == 0            # too few rows to split
+    assert axo.axo_bias_grad_workspace_bytes(mk(255, 24)) == 0
+    assert axo.axo_bias_grad_workspace_bytes(mk(256, 24)) == 256 + 2 * 24 * 4
+    assert axo.axo_bias_grad_workspace_bytes(axo.Problem.make((0, 1, 1), (0, 0, 0), 8, 8, 8)) == 0   # invalid problem
+    p = mk(4096, 6144)
+    need = axo.axo_bias_grad_workspace_bytes(p)
+    B1, B2 = 1 << 40, 2 << 40                                             # far beyond dY's 50 MB
+    f = lambda **kw: axo.axo_bias_grad_ws(**{**dict(p=p, dY=A, lddy=6144, db=B1, accumulate=0, ws=B2, ws_bytes=need,
+                                                    check=False), **kw})
+    assert f(ws=None) == WORKSPACE and f(ws_bytes=need - 1) == WORKSPACE and f(ws=B2 + 8) == MISALIGNED
+    assert f(db=None) == NULL_PTR and f(lddy=6136) == BAD_LD and f(accumulate=3) == BAD_ARG
+    assert f(db=A + 128) == BAD_ARG                                       # db inside dY
+    # nothing to do: valid without a device or a workspace
+    assert axo.axo_bias_grad_ws(mk(64, 0), A, 8, A1, 0, None, 0, check=False) == OK
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py measures one GPU's share; asked for more it has to say so and exit non-zero
     (decided before anything touches a GPU, so this runs anywhere)."""

@@ -142,6 +142,62 @@ def test_bias_grad(M, Nl):
     assert torch.equal(db2, db3)
 
 
+@pytest.mark.parametrize("M,Nl", [(256, 256), (4096, 1536), (4096, 6144), (300, 136), (77, 24), (1, 8), (1000, 40),
+                                  (513, 4104), (8192, 3584), (100000, 64), (129, 72)])
+def test_bias_grad_with_rows_split_over_workgroups(M, Nl):
+    """axo_bias_grad_ws against the fp64 oracle: slices of rows per strip, partial sums in the workspace, the
+    last workgroup of a strip adds them in slice order.  The workspace is zero-filled once; every call has
+    to leave its arrival counters at zero, which the repeated calls on the same workspace rely on."""
+    dYb = syn.normal_bf16(26, 0, (M, Nl), 1.0)
+    dY = gu.to_dev(dYb)
+    p = P(M, 8, Nl)
+    nws = axo.axo_bias_grad_workspace_bytes(p)
+    ws = torch.zeros(max(nws, 16), dtype=torch.uint8, device="cuda:0")
+    wsp = ws.data_ptr() if nws else None
+    db = torch.full((Nl,), float("nan"), dtype=torch.float32, device="cuda:0")
+    axo.axo_bias_grad_ws(p, dY.data_ptr(), Nl, db.data_ptr(), 0, wsp, nws, gu.stream())
+    torch.cuda.synchronize()
+    ref = oracle.bias_grad(dYb)
+    tol = 4e-6 * np.sqrt(M) * 4 + 1e-6           # fp32 sums of M values of unit scale
+    got = db.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got - ref)) <= tol, np.max(np.abs(got - ref))
+    n_strips = (Nl + 63) // 64
+    assert int(ws[:4 * n_strips].view(torch.int32).abs().max()) == 0 if nws else True   # counters back at zero
+    axo.axo_bias_grad_ws(p, dY.data_ptr(), Nl, db.data_ptr(), 1, wsp, nws, gu.stream())   # accumulate on top
+    torch.cuda.synchronize()
+    assert np.max(np.abs(db.cpu().numpy().astype(np.float64) - 2 * ref)) <= 2 * tol
+    # run to run identical, whichever workgroup arrives last (fixed summation order, no float atomics)
+    # (many back-to-back calls: a slice sum read before it was published would show up here)
+    outs = []
+    for _ in range(60):
+        o = torch.zeros_like(db)
+        axo.axo_bias_grad_ws(p, dY.data_ptr(), Nl, o.data_ptr(), 0, wsp, nws, gu.stream())
+        outs.append(o)
+    torch.cuda.synchronize()
+    assert all(torch.equal(outs[0], o) for o in outs[1:])
+
+
+def test_bias_grad_split_in_place_columns_and_smaller_second_call():
+    """A column block addressed inside a wider matrix, then a smaller problem on the same workspace."""
+    M, N = 1024, 2048
+    dYb = syn.normal_bf16(27, 0, (M, N), 1.0)
+    dY = gu.to_dev(dYb)
+    p = axo.Problem.make((1, 4, 1), (0, 2, 0), M, 8, N)
+    nws = axo.axo_bias_grad_workspace_bytes(p)
+    assert nws > 0
+    ws = torch.zeros(nws, dtype=torch.uint8, device="cuda:0")
+    db = torch.zeros(512, dtype=torch.float32, device="cuda:0")
+    axo.axo_bias_grad_ws(p, dY[:, 1024:].data_ptr(), N, db.data_ptr(), 0, ws.data_ptr(), nws, gu.stream())
+    p2 = axo.Problem.make((1, 8, 2), (0, 1, 1), M, 8, N)
+    nws2 = axo.axo_bias_grad_workspace_bytes(p2)
+    assert 0 < nws2 <= nws
+    db2 = torch.zeros(256, dtype=torch.float32, device="cuda:0")
+    axo.axo_bias_grad_ws(p2, dY[512:, 256:].data_ptr(), N, db2.data_ptr(), 0, ws.data_ptr(), nws, gu.stream())
+    torch.cuda.synchronize()
+    assert np.max(np.abs(db.cpu().numpy() - oracle.bias_grad(dYb[:, 1024:1536]))) <= 1e-3
+    assert np.max(np.abs(db2.cpu().numpy() - oracle.bias_grad(dYb[512:, 256:512]))) <= 1e-3
+
+
 def test_bias_grad_in_place_columns():
     M, N = 384, 1024
     dYb = syn.normal_bf16(25, 0, (M, N), 1.0)
