@@ -65,7 +65,8 @@ typedef enum axo_status {
     AXO_ERR_HIP = -9,          /* a HIP launch failed (the only status that needs a device)      */
     AXO_ERR_BAD_SIZE = -10,    /* T, K or N < 0, or a shard dimension beyond 2^31-1              */
     AXO_ERR_BAD_ARG = -11,     /* anything else malformed (unknown op, n_layers < 0, ...)        */
-    AXO_ERR_NO_MEMORY = -12    /* a host allocation of the library failed (plan lists, caches)   */
+    AXO_ERR_NO_MEMORY = -12,   /* a host allocation of the library failed (plan lists, caches)   */
+    AXO_ERR_TOO_LARGE = -13    /* more scratch needed than the allocation-free entry point holds */
 } axo_status_t;
 
 /* The problem statement of Section 3.2: grid, this GPU's coordinate, global sizes. */
@@ -204,6 +205,24 @@ size_t axo_bias_grad_workspace_bytes(const axo_problem_t *p);
  * Errors: those of axo_bias_grad; WORKSPACE (ws NULL or too small); MISALIGNED (ws). */
 int axo_bias_grad_ws(const axo_problem_t *p, const void *dY, int64_t lddy, float *db, int accumulate,
                      void *ws, size_t ws_bytes, void *hip_stream);
+
+/* axo_bias_grad_ws for callers that cannot allocate device memory or pass a workspace along: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernel, same
+ * slicing, same bits as axo_bias_grad_ws; the slice sums and arrival counters live in a fixed array
+ * of axo_bias_grad_static_limit() bytes (256 KiB) inside the library's device image instead of a
+ * workspace.  Each GPU the library runs on holds its own copy of that array from the first use to
+ * the end of the process.  The call allocates nothing (no hipMalloc, no hipFree, no host
+ * containers); on its first use on a device it asks the runtime once for the array's address there.
+ * The array is shared by all calls on a GPU and keeps their contents: the counters are zero when
+ * the library is loaded and every call returns them to zero, the slice sums need no clearing.  Two
+ * calls that overlap in time on one GPU (different streams without an ordering) race on it.
+ * Errors: those of axo_bias_grad; TOO_LARGE when axo_bias_grad_workspace_bytes(p) exceeds the limit
+ * (with today's slicing no shape needs more than 132 KiB, so none is refused); HIP. */
+int axo_bias_grad_static(const axo_problem_t *p, const void *dY, int64_t lddy, float *db, int accumulate,
+                         void *hip_stream);
+
+/* Host only.  Size in bytes of the fixed scratch array of axo_bias_grad_static. */
+size_t axo_bias_grad_static_limit(void);
 
 /* One FC layer of a chain: its problem, epilogue, and the caller's buffers with their leading
  * dimensions.  X and W are kept by the caller between forward and backward (the cache of

@@ -112,6 +112,9 @@ def library() -> ctypes.CDLL:
     L.axo_bias_grad_workspace_bytes.restype = sz
     L.axo_bias_grad_ws.argtypes = [PP, vp, i64, vp, i32, vp, sz, vp]
     L.axo_bias_grad_ws.restype = i32
+    L.axo_bias_grad_static.argtypes = [PP, vp, i64, vp, i32, vp]
+    L.axo_bias_grad_static.restype = i32
+    L.axo_bias_grad_static_limit.restype = sz
     L.axo_layer_step_ext.argtypes = [ctypes.POINTER(LayerExt), i32, vp, sz, vp]
     L.axo_layer_step_ext.restype = i32
     L.axo_layer_step_ordered.argtypes = [ctypes.POINTER(Layer), i32, vp, sz, vp]
@@ -246,3 +249,13 @@ def axo_bias_grad_ws(p: Problem, dY: int, lddy: int, db: int, accumulate: int = 
                      ws_bytes: int = 0, stream: Optional[int] = None, check: bool = True) -> int:
     rc = library().axo_bias_grad_ws(ctypes.byref(p), dY, lddy, db, accumulate, ws, ws_bytes, stream)
     return _check(rc, "axo_bias_grad_ws", check)
+
+
+def axo_bias_grad_static(p: Problem, dY: int, lddy: int, db: int, accumulate: int = 0, stream: Optional[int] = None,
+                         check: bool = True) -> int:
+    rc = library().axo_bias_grad_static(ctypes.byref(p), dY, lddy, db, accumulate, stream)
+    return _check(rc, "axo_bias_grad_static", check)
+
+
+def axo_bias_grad_static_limit() -> int:
+    return int(library().axo_bias_grad_static_limit())

@@ -22,6 +22,14 @@
 #include "gemm_generic.hpp"
 #include "gemm_tile.hpp"
 
+// Scratch memory of the allocation-free entry point (axo_bias_grad_static): arrival counters and
+// slice sums of the split bias gradient, laid out as BiasSplit says.  One copy per GPU, held from
+// the moment the library is loaded on it until the process ends; zero-initialised by the loader,
+// and every call leaves the counters at zero.  In host code this name only stands for the symbol:
+// the device address comes from hipGetSymbolAddress (static_scratch() below), per device.
+constexpr size_t STATIC_SCRATCH_BYTES = 256 * 1024;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using axo::GemmArgs;
@@ -599,6 +607,26 @@ int launch_bias_grad_split(const axo::BiasGradArgs& g, const BiasSplit& b, void*
     return hipGetLastError() == hipSuccess ? AXO_OK : AXO_ERR_HIP;
 }
 
+// Device address of this GPU's copy of `scratch`: asked for once per device, with that device
+// current, and kept (each GPU holds its own copy at its own address).  No allocation.
+int static_scratch(void** out) {
+    static std::atomic<void*> known[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return AXO_ERR_HIP;
+    const bool slot = dev >= 0 && dev < 64;
+    if (slot) {
+        if (void* p = known[dev].load(std::memory_order_acquire)) {
+            *out = p;
+            return AXO_OK;
+        }
+    }
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return AXO_ERR_HIP;
+    if (slot) known[dev].store(p, std::memory_order_release);
+    *out = p;
+    return AXO_OK;
+}
+
 // one unit of work on its own
 int launch_plan(const Plan& pl, hipStream_t st) {
     return pl.bias_grad ? launch_bias_grad(pl.bg, st) : launch(pl.g, pl.la, pl.lb, st);
@@ -918,6 +946,7 @@ const char* axo_status_string(int status) {
         case AXO_ERR_BAD_SIZE: return "negative size or shard dimension beyond 2^31-1";
         case AXO_ERR_BAD_ARG: return "malformed argument";
         case AXO_ERR_NO_MEMORY: return "host allocation failed";
+        case AXO_ERR_TOO_LARGE: return "problem needs more scratch memory than the allocation-free entry point holds";
         default: return "unknown status";
     }
 }
@@ -1037,6 +1066,24 @@ int axo_bias_grad_ws(const axo_problem_t* p, const void* dY, int64_t lddy, float
     }
     return launch_bias_grad_split(pl.bg, b, ws, static_cast<hipStream_t>(hip_stream));
 }
+
+int axo_bias_grad_static(const axo_problem_t* p, const void* dY, int64_t lddy, float* db, int accumulate,
+                         void* hip_stream) {
+    Plan pl;
+    const int rc = plan_bias_grad(p, dY, lddy, db, accumulate, &pl);
+    if (rc) return rc;
+    if (pl.bg.Nl == 0) return AXO_OK;
+    const BiasSplit b = plan_bias_split(pl.bg.M, pl.bg.Nl);
+    if (b.bytes() > STATIC_SCRATCH_BYTES) return AXO_ERR_TOO_LARGE;
+    void* dev_scratch = nullptr;
+    if (b.bytes() > 0) {
+        const int sc = static_scratch(&dev_scratch);
+        if (sc) return sc;
+    }
+    return launch_bias_grad_split(pl.bg, b, dev_scratch, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t axo_bias_grad_static_limit(void) { return STATIC_SCRATCH_BYTES; }
 
 size_t axo_layer_step_workspace_bytes(const axo_layer_t* layers, int n_layers) {
     size_t need = 0;

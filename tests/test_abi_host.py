@@ -14,8 +14,8 @@ import paper_2305_13525_amd as axo
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "axo.h")
 
-OK, BAD_GRID, BAD_COORD, INDIVISIBLE, NULL_PTR, MISALIGNED, BAD_LD, WORKSPACE, BAD_EPI, HIP, BAD_SIZE, BAD_ARG, NO_MEMORY = (
-    0, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10, -11, -12)
+OK, BAD_GRID, BAD_COORD, INDIVISIBLE, NULL_PTR, MISALIGNED, BAD_LD, WORKSPACE, BAD_EPI, HIP, BAD_SIZE, BAD_ARG, NO_MEMORY, TOO_LARGE = (
+    0, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10, -11, -12, -13)
 
 
 def declared_functions():
@@ -50,7 +50,7 @@ def test_struct_layout_matches_header():
 
 def test_status_strings():
     seen = set()
-    for s in range(0, -12, -1):
+    for s in range(0, -14, -1):
         t = axo.axo_status_string(s)
         assert t and t != "unknown status" and t not in seen
         seen.add(t)
