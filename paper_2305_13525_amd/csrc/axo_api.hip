@@ -103,12 +103,13 @@ bool span_ok(int layout, int64_t ld, int64_t R) {
     return elems * 2 < (int64_t)0xFFFF0000;
 }
 
-// Reductions: multiples of 128 (the loop is unrolled over two 64-wide LDS stages), except where
-// both operands have the reduction index as their row index (wgrad): there the kernel rounds the
-// length up itself and reads the surplus rows as zeros, so any length goes.
+// Reductions: any length where both operands have the reduction index as their row index (wgrad:
+// rows beyond the end read as zeros through the buffer bound); any multiple of 8 otherwise (an
+// operand with the reduction inside its rows has its last fragments masked in registers, which
+// needs whole 16-byte fragments).  The kernel walks the length rounded up to 128.
 bool tileable(const GemmArgs& g, int la, int lb) {
     const bool any_reduction = la == axo::MC && lb == axo::MC;
-    if (!(g.R > 0 && (any_reduction || g.R % (2 * axo::TILE_BK) == 0) && g.Mo > 0 && g.No > 0 && g.Mo % 256 == 0 &&
+    if (!(g.R > 0 && (any_reduction || g.R % 8 == 0) && g.Mo > 0 && g.No > 0 && g.Mo % 256 == 0 &&
           g.No % 128 == 0))
         return false;
     // the span is that of the rows the kernel walks: the reduction rounded up to the unrolled loop's

@@ -1,5 +1,6 @@
-// Tuned bf16 MFMA GEMM for gfx950 (MI355X) for shapes that are whole multiples of the tile:
-//   C[Mo x No] = sum_r A(i, r) * B(j, r),  Mo % 256 == 0, No % 128 == 0, R % 128 == 0.
+// Tuned bf16 MFMA GEMM for gfx950 (MI355X) for outputs that are whole multiples of the tile:
+//   C[Mo x No] = sum_r A(i, r) * B(j, r),  Mo % 256 == 0, No % 128 == 0; the reduction length R is
+//   any multiple of 8 (any length at all when both operands have it as their row index).
 // Tile counts that do not fill the last round of CUs are balanced by covering part of the output
 // with half-width tiles (TileSched).
 //
@@ -241,24 +242,28 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
-    // Both operands of wgrad have the reduction index as their row index (MC).  Rows at or beyond
-    // the end of the reduction can then be made to read as zeros by the buffer descriptor's range
-    // check, so that instantiation takes ANY reduction length: it walks the length rounded up to
-    // the next multiple of 128 and the surplus rows contribute nothing.  (A KC operand has the
-    // reduction inside its rows; its overrun lands in the next row, which no linear bound can mask,
-    // so the other products keep to multiples of 128.)
-    constexpr bool CLAMPED = (LA == MC && LB == MC);
-    const int KT = CLAMPED ? (g.R + 2 * TILE_BK - 1) / (2 * TILE_BK) * 2 : g.R / TILE_BK;
+    // The loop is unrolled over the two LDS stages, so it walks the reduction rounded up to the
+    // next multiple of 128; what lies beyond the true length must contribute nothing, whatever
+    // the memory there holds (zeros would do for finite data, but a stray infinity times a zero
+    // of the other operand would put a NaN into a row that has none: BOTH operands are made zero).
+    //  * MC operand (reduction index = row index): rows at or beyond R lie behind the buffer
+    //    descriptor's bound, the byte count from the tile origin to the end of the tile's columns
+    //    in row R - 1, and read as zeros.
+    //  * KC operand (reduction inside the rows): the overrun of a row lands in the next row,
+    //    which no linear bound can mask; the surplus 16-byte chunks of the last two steps are
+    //    overwritten with zeros in LDS instead (R is a multiple of 8 here, so a chunk is wholly
+    //    inside or wholly outside).  The bound (end of the tile's last row) only keeps the last
+    //    row's overrun from touching memory behind the matrix.
+    // On this chip the range check covers the sum of the per-lane offset and the scalar offset
+    // that carries the reduction step (measured: lowering the bound by the scalar offset at every
+    // step zeroed the second half of the reduction), so one constant bound serves the whole walk.
+    const int KT = (g.R + 2 * TILE_BK - 1) / (2 * TILE_BK) * 2;
+    const bool tail = (g.R % (2 * TILE_BK)) != 0;
 
     // global side: descriptor at the tile origin, per-lane offsets, scalar step
     const bf16_t* Ab = (LA == KC) ? g.A + (int64_t)i0 * g.lda : g.A + i0;
     const bf16_t* Bb = (LB == KC) ? g.B + (int64_t)j0 * g.ldb : g.B + j0;
-    // raw buffer descriptor: base, stride 0, dword format.  Bound: none for KC operands (the host
-    // checked the spans).  For the clamped instantiation the bound is the number of bytes from the
-    // tile origin to the end of the tile's columns in the last row of the reduction.  On this
-    // chip the range check covers the sum of the per-lane offset and the scalar offset that
-    // carries the reduction step (measured: lowering the bound by the scalar offset at every step
-    // zeroed the second half of the reduction), so one constant bound serves the whole walk.
+    // raw buffer descriptor: base, stride 0, dword format, bound in bytes
     auto make_rsrc = [](const bf16_t* p, uint32_t bound) __attribute__((always_inline)) {
         const uint64_t v = reinterpret_cast<uint64_t>(p);
         u32x4_t r;
@@ -268,8 +273,10 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
         r[3] = 0x00020000u;
         return r;
     };
-    const uint32_t a_valid = CLAMPED ? (uint32_t)((((int64_t)g.R - 1) * g.lda + BM) * 2) : 0xFFFFFFFFu;
-    const uint32_t b_valid = CLAMPED ? (uint32_t)((((int64_t)g.R - 1) * g.ldb + BN) * 2) : 0xFFFFFFFFu;
+    const uint32_t a_valid = (LA == KC) ? (uint32_t)(((int64_t)(BM - 1) * g.lda + g.R) * 2)
+                                        : (uint32_t)((((int64_t)g.R - 1) * g.lda + BM) * 2);
+    const uint32_t b_valid = (LB == KC) ? (uint32_t)(((int64_t)(BN - 1) * g.ldb + g.R) * 2)
+                                        : (uint32_t)((((int64_t)g.R - 1) * g.ldb + BN) * 2);
     const u32x4_t a_rsrc = make_rsrc(Ab, a_valid);
     const u32x4_t b_rsrc = make_rsrc(Bb, b_valid);
     const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
@@ -366,7 +373,33 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     // waves of a SIMD the one that lags is then preferred by the MFMA arbiter, which keeps them
     // from serialising (measured: without this one wave of each SIMD waits at the barrier for
     // about 40 % of the step while the other one is starved of MFMA issue slots).
-    auto step = [&](auto s_tag, const bool head, const bool load, const bool next) __attribute__((always_inline)) {
+    // A reduction that ends inside the last two steps: the 16-byte chunks of a KC operand that lie
+    // beyond its end are overwritten with zeros in LDS once the stage has landed, by the lane
+    // that fetched them (round j of thread tid filled slot q = j * 512 + tid of the tile: row
+    // q / 8, LDS chunk q % 8, which holds global chunk (q % 8) ^ swz_kc(row), i.e. reduction
+    // elements 8 * that onwards).  `rem` = reduction elements of the stage that are real.
+    auto zero_tail = [&](auto s_tag, const int rem) __attribute__((always_inline)) {
+        constexpr int s = decltype(s_tag)::value;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        if (LA == KC) {
+#pragma unroll
+            for (int j = 0; j < C::A_ROUNDS; ++j) {
+                const int q = j * TILE_THREADS + tid, r = q >> 3, cs = q & 7;
+                if (((cs ^ swz_kc(r)) << 3) >= rem) *reinterpret_cast<u32x4*>(smem + s * C::A_BYTES + q * 16) = zero;
+            }
+        }
+        if (LB == KC) {
+#pragma unroll
+            for (int j = 0; j < C::B_ROUNDS; ++j) {
+                const int q = j * TILE_THREADS + tid, r = q >> 3, cs = q & 7;
+                if (((cs ^ swz_kc(r)) << 3) >= rem)
+                    *reinterpret_cast<u32x4*>(smem + 2 * C::A_BYTES + s * C::B_BYTES + q * 16) = zero;
+            }
+        }
+    };
+    // `fix` (first of the two tail steps only): stage s^1 holds the last step, which has just
+    // landed; its chunks beyond the end of the reduction are zeroed before the barrier publishes it.
+    auto step = [&](auto s_tag, const bool head, const bool load, const bool next, const bool fix) __attribute__((always_inline)) {
         constexpr int s = decltype(s_tag)::value;
         AXO_SETPRIO(2);
         if (head) issue_range(IC<E4>{}, IC<E1>{}, s ^ 1);
@@ -387,6 +420,7 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
         mfma_group(0, 1, 0);  // (kq 1, ah 0)
         Interleave<N_MFMA, 0, RD_A, 0>::run();
         __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+        if (fix) zero_tail(IC<s ^ 1>{}, g.R - (KT - 1) * TILE_BK);
         __syncthreads();
         AXO_SETPRIO(3);
         if (load) issue_range(IC<0>{}, IC<E4>{}, s);
@@ -400,7 +434,7 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     using T0 = std::integral_constant<int, 0>;
     using T1 = std::integral_constant<int, 1>;
 
-    // KT is even and at least 2 (the host only sends reductions that are multiples of 128 here)
+    // KT is even and at least 2
     issue_range(IC<0>{}, IC<NL>{}, 0);
     advance();
     issue_range(IC<0>{}, IC<E4>{}, 1);  // step 0 issues the rest of stage 1
@@ -409,11 +443,22 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int i0, 
     read_a(0, 0, 0, 0);
     read_b(0, 0, 0);
     for (int j = 0; j + 2 < KT; j += 2) {  // steady state, branch free: steps j, j+1; refills j+2, j+3
-        step(T0{}, true, true, true);
-        step(T1{}, true, true, true);
+        step(T0{}, true, true, true, false);
+        step(T1{}, true, true, true, false);
     }
-    step(T0{}, true, false, true);  // the last two steps: nothing left to load
-    step(T1{}, false, false, false);
+    // The last two steps: nothing left to load.  Step KT-2 sits in stage 0, landed and published
+    // (by the barrier of the step before, or the one above); where the reduction ends inside it
+    // its surplus chunks are zeroed now, behind a barrier of their own, and the fragments that
+    // were read ahead are read again.
+    const bool fix = (LA == KC || LB == KC) && tail;
+    if (fix) {
+        zero_tail(T0{}, g.R - (KT - 2) * TILE_BK);
+        __syncthreads();
+        read_a(0, 0, 0, 0);
+        read_b(0, 0, 0);
+    }
+    step(T0{}, true, false, true, fix);
+    step(T1{}, false, false, false, false);
     AXO_SETPRIO(0);
 
     // ---- epilogue: acc[a][b][e] is C[i0 + wm*WTM + a*16 + lane%16][j0 + wn*WTN + b*16 + 4*(lane/16) + e]

@@ -85,7 +85,11 @@ RAGGED = [(1, 8, 8), (1000, 520, 264), (130, 40, 72), (257, 264, 136), (77, 1000
           (1030, 512, 1160),
           # token counts (the reduction of wgrad) of any length, odd ones included: the wgrad kernel
           # rounds the reduction up itself and reads the surplus rows as zeros
-          (1000, 256, 384), (77, 256, 128), (1, 256, 128), (129, 512, 256), (4101, 256, 640), (300, 264, 136)]
+          (1000, 256, 384), (77, 256, 128), (1, 256, 128), (129, 512, 256), (4101, 256, 640), (300, 264, 136),
+          # reductions of forward (Kl) and dgrad (Nl) that are multiples of 8 but not of 128, on tile-multiple
+          # outputs and on ragged ones: the tuned kernel walks them rounded up and zeroes the surplus in LDS
+          (256, 200, 128), (256, 128, 200), (512, 328, 392), (256, 8, 136), (256, 136, 8), (512, 1928, 256),
+          (256, 256, 1928), (768, 2000, 520), (1000, 72, 1016), (256, 64, 120), (256, 192, 448)]
 
 
 @pytest.mark.parametrize("M,Kl,Nl", RAGGED)
@@ -110,6 +114,39 @@ def test_ragged_and_tile_edge_shapes(M, Kl, Nl):
     gu.assert_close(oracle, dWh[:, :Nl], oracle.fc_wgrad(Xb, dYb), "wgrad")
     # nothing outside the logical matrix was written (the pad keeps its NaN fill)
     assert (Yh[:, Nl:] == 0x7FC0).all() and (dXh[:, Kl:] == 0x7FC0).all() and (dWh[:, Nl:] == 0x7FC0).all()
+
+
+def test_reduction_tails_ignore_what_lies_behind_them():
+    """Forward and dgrad with reductions that end inside the tuned kernel's last steps (2000 and 1928:
+    16 resp. 8 real elements in the last but one step of 64, none in the last).  The shards sit in place
+    inside wider buffers whose neighbouring columns and rows hold NaNs and infinities: what the kernel
+    walks beyond the end of the reduction must not reach the result (a zero times a stray infinity would
+    put a NaN into a row that has none), bit for bit the result of clean, contiguous operands."""
+    for (M, Kl, Nl) in ((512, 2000, 256), (256, 256, 1928), (512, 328, 392)):
+        Xb, Wb, dYb = rand_trio(M, Kl, Nl, 300 + Kl)
+        p = P(M, Kl, Nl)
+        poison = np.array([0x7FC0, 0x7F80, 0xFF80, 0x7FC1], dtype=np.uint16)
+
+        def inside(bits, rows, cols):
+            """bits in the top-left corner of a [rows, cols] buffer filled with NaN / inf patterns"""
+            big = np.tile(poison, (rows * cols + 3) // 4)[:rows * cols].reshape(rows, cols).copy()
+            big[:bits.shape[0], :bits.shape[1]] = bits
+            return gu.to_dev(big)
+
+        Xw, Ww, dYw = inside(Xb, M + 8, Kl + 136), inside(Wb, Kl + 136, Nl + 136), inside(dYb, M + 8, Nl + 136)
+        Xs, Ws, dYs = Xw[:M, :Kl], Ww[:Kl, :Nl], dYw[:M, :Nl]
+        assert axo.axo_fc_route(p, axo.AXO_OP_FWD, gu.ld(Xs), gu.ld(Ws), Nl)[1] in (axo.AXO_ROUTE_TILED, axo.AXO_ROUTE_COVERED)
+        assert axo.axo_fc_route(p, axo.AXO_OP_DGRAD, gu.ld(dYs), gu.ld(Ws), Kl)[1] in (axo.AXO_ROUTE_TILED, axo.AXO_ROUTE_COVERED)
+        Y, dX, dW = gu.empty_dev(M, Nl), gu.empty_dev(M, Kl), gu.empty_dev(Kl, Nl)
+        keep = [gu.run_fwd(p, Xs, Ws, Y), gu.run_dgrad(p, dYs, Ws, dX), gu.run_wgrad(p, Xs, dYs, dW)]
+        torch.cuda.synchronize()
+        del keep
+        Yc, dXc, dWc = gu.trio(p, Xb, Wb, dYb)       # the same products on clean, contiguous operands
+        for name, got, clean, ref in (("fwd", Y, Yc, oracle.fc_fwd(Xb, Wb)), ("dgrad", dX, dXc, oracle.fc_dgrad(dYb, Wb)),
+                                      ("wgrad", dW, dWc, oracle.fc_wgrad(Xb, dYb))):
+            got = gu.to_host(got)
+            gu.assert_close(oracle, got, ref, f"{name} {(M, Kl, Nl)} inside poisoned buffers")
+            assert np.array_equal(got, clean), name
 
 
 def test_empty_dimensions():
