@@ -35,16 +35,23 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
 PEAK_HBM_GBPS = 8000.0
 
-# HBM-side bytes per launch (fetched + written) of the tuned kernel, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this script (the summaries under profiles/ give the commands), scaled by the same
-# counters' readings for a plain 1 GiB copy (2.000 KiB per FETCH_SIZE count, 1.000 KiB per WRITE_SIZE
-# count).  Keyed by (workload, product); "group" is the single launch of the grouped step.
-MEASURED_TRAFFIC_BYTES = {
-    ("cfg2", "fwd"): int((82100.9 * 2.0 + 49152.0) * 1024),
-    ("cfg2", "dgrad"): int((98372.0 * 2.0 + 16385.4) * 1024),
-    ("cfg2", "wgrad"): int((82012.6 * 2.0 + 24581.5) * 1024),
-    ("cfg2", "group"): int((305489.7 * 2.0 + 90116.2) * 1024),
+# HBM-side traffic per launch of the tuned kernels, as (FETCH_SIZE, WRITE_SIZE) counter readings from
+# rocprofv3 --pmc runs of this script (profiles/gemm_kernels_cfg*.md give the commands and the tables),
+# scaled by the same counters' readings for a plain 1 GiB copy: 2.000 KiB per FETCH_SIZE count, 1.000 KiB
+# per WRITE_SIZE count.  Keyed by (workload, product); "group" is the single launch of the grouped step.
+FETCH_KIB_PER_COUNT, WRITE_KIB_PER_COUNT = 2.0, 1.0
+MEASURED_TRAFFIC_COUNTS = {
+    ("cfg2", "group"): (304921.3, 90119.7), ("cfg2", "fwd"): (82080.7, 49152.0),
+    ("cfg2", "dgrad"): (98381.9, 16385.4), ("cfg2", "wgrad"): (82010.5, 24586.6),
+    ("cfg3", "group"): (781223.8, 213003.4), ("cfg3", "fwd"): (196811.0, 131097.4),
+    ("cfg3", "dgrad"): (270116.8, 16393.6), ("cfg3", "wgrad"): (196698.5, 65537.3),
+    ("cfg4", "group"): (782209.2, 213013.9), ("cfg4", "fwd"): (267810.6, 16384.4),
+    ("cfg4", "dgrad"): (196709.5, 131100.1), ("cfg4", "wgrad"): (196698.5, 65536.6),
+    ("cfg5", "group"): (1105521.4, 251937.3), ("cfg5", "fwd"): (61680.1, 49152.4),
+    ("cfg5", "dgrad"): (86082.5, 12288.0), ("cfg5", "wgrad"): (83034.5, 18435.7),
 }
+MEASURED_TRAFFIC_BYTES = {k: int((f * FETCH_KIB_PER_COUNT + w * WRITE_KIB_PER_COUNT) * 1024)
+                          for k, (f, w) in MEASURED_TRAFFIC_COUNTS.items()}
 
 HEADLINE = "cfg3"
 ALSO = ("cfg2", "cfg4", "cfg5")
