@@ -30,8 +30,9 @@
  * Ownership: the caller owns all buffers; the library allocates no device memory, keeps no pointer after
  * a call returns, and only enqueues work on the caller's HIP stream (no device synchronisation,
  * no host read-back).  Buffers must stay valid until the stream has executed the call.
- * The output of a product must not overlap an input of the same product.  A matrix with no elements (a zero shard dimension) is never
- * dereferenced: its pointer may be NULL and its leading dimension is not checked.
+ * The output of a product must not share a byte with an input of the same product (checked: AXO_ERR_BAD_ARG;
+ * column blocks of one buffer that merely interleave are fine).  A matrix with no elements (a zero shard
+ * dimension) is never dereferenced: its pointer may be NULL and its leading dimension is not checked.
  *
  * Errors: every function returns an int status, 0 on success, negative on error; nothing throws
  * or aborts.  All argument checks happen on the host before the first HIP call, so every status
@@ -139,7 +140,12 @@ int axo_fc_route(const axo_problem_t *p, int op, int64_t ld_a, int64_t ld_b, int
  * hipStream_t (NULL = the default stream).  A shard with M, Kl or Nl == 0 is valid: with
  * Kl == 0 the output is epilogue(0); with M or Nl == 0 nothing is written.
  * Errors: those of axo_shard_dims; BAD_EPILOGUE (unknown epilogue, or one with bias == NULL);
- * NULL_PTR, BAD_LD, MISALIGNED for X, W, Y, bias; WORKSPACE; HIP; NO_MEMORY. */
+ * NULL_PTR, BAD_LD, MISALIGNED for X, W, Y, bias; BAD_ARG (Y shares bytes with X, W or bias); WORKSPACE;
+ * HIP; NO_MEMORY.
+ * Speed: the tuned kernel takes shards whose reduction length (Kl here, Nl for dgrad) is a multiple of 8 and
+ * whose output has at least 256 rows and 128 columns, the column count a multiple of 8; leading dimensions
+ * that are multiples of 64 elements keep every 128-byte row segment inside one cache line (worth 10-20 %).
+ * Everything else is computed by a general kernel that is several times slower; axo_fc_route tells which. */
 int axo_fc_fwd(const axo_problem_t *p, const void *X, int64_t ldx, const void *W, int64_t ldw,
                const void *bias, int epilogue, void *Y, int64_t ldy,
                void *ws, size_t ws_bytes, void *hip_stream);
@@ -215,7 +221,8 @@ int axo_bias_grad_ws(const axo_problem_t *p, const void *dY, int64_t lddy, float
  * containers); on its first use on a device it asks the runtime once for the array's address there.
  * The array is shared by all calls on a GPU and keeps their contents: the counters are zero when
  * the library is loaded and every call returns them to zero, the slice sums need no clearing.  Two
- * calls that overlap in time on one GPU (different streams without an ordering) race on it.
+ * calls that overlap in time on one GPU (different streams without an ordering) race on it.  The address
+ * lookup is not a stream operation; make the first call on a device outside any stream capture.
  * Errors: those of axo_bias_grad; TOO_LARGE when axo_bias_grad_workspace_bytes(p) exceeds the limit
  * (with today's slicing no shape needs more than 132 KiB, so none is refused); HIP. */
 int axo_bias_grad_static(const axo_problem_t *p, const void *dY, int64_t lddy, float *db, int accumulate,

@@ -15,7 +15,8 @@ import gpu_util as gu  # noqa: E402
 
 SHAPES = [(256, 256, 256), (512, 384, 640), (300, 72, 136), (1024, 128, 1280), (77, 40, 24), (768, 256, 1152),
           (520, 264, 384), (384, 264, 136),   # tuned interior plus strips or bands
-          (1000, 256, 384)]                   # wgrad on the tuned kernel with a reduction that is no multiple of 128
+          (1000, 256, 384),                   # wgrad on the tuned kernel with a reduction that is no multiple of 128
+          (512, 256, 328), (768, 392, 1928)]  # dgrad (reduction Nl) with a tail on the tuned kernel
 
 
 def P(M, Kl, Nl):

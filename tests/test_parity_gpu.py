@@ -178,7 +178,8 @@ def test_empty_dimensions():
 
 
 @pytest.mark.parametrize("epi", [axo.AXO_EPI_BIAS, axo.AXO_EPI_BIAS_GELU_TANH, axo.AXO_EPI_BIAS_GELU_ERF])
-@pytest.mark.parametrize("shape", [(200, 136, 264), (512, 256, 512), (520, 256, 392)])   # the last: interior + strips
+@pytest.mark.parametrize("shape", [(200, 136, 264), (512, 256, 512), (520, 256, 392),   # the third: a covered output
+                                   (512, 200, 256), (768, 1928, 392)])                  # reductions with a tail
 def test_forward_epilogues(epi, shape):
     M, Kl, Nl = shape
     Xb = syn.normal_bf16(5, 0, (M, Kl), 1.0)
@@ -329,7 +330,8 @@ def test_rounding_is_nearest_even():
 def test_grouped_step_mixed_shapes_against_oracle():
     """axo_layer_step on an independent chain that mixes shapes the tiled kernel takes, shapes it does not
     (ragged; a product with a 128-row output) and an empty layer: every element against the oracle."""
-    shapes = [(256, 256, 256), (300, 72, 136), (256, 128, 384), (512, 384, 640), (0, 64, 64), (768, 256, 1152)]
+    shapes = [(256, 256, 256), (300, 72, 136), (256, 128, 384), (512, 384, 640), (0, 64, 64), (768, 256, 1152),
+              (512, 328, 392), (256, 200, 1928)]   # reductions that end inside the tuned kernel's last steps
     layers, keep = [], []
     for i, (M, Kl, Nl) in enumerate(shapes):
         Xb, Wb, dYb = rand_trio(M, Kl, Nl, 900 + i)
