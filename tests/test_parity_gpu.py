@@ -149,6 +149,24 @@ def test_reduction_tails_ignore_what_lies_behind_them():
             assert np.array_equal(got, clean), name
 
 
+def test_seeded_random_shapes_against_oracle():
+    """Twenty-four seeded shapes with row lengths that are multiples of 8 (what the tuned kernel asks for),
+    drawn so that every route occurs: whole tiles, covered outputs, reductions with tails, and the general
+    kernel for the small ones.  Every element of all three products against the oracle."""
+    rng = np.random.default_rng(20240)
+    routes = set()
+    for case in range(24):
+        M = int(rng.choice([rng.integers(1, 300), rng.integers(256, 1100), 256 * rng.integers(1, 5)]))
+        Kl = int(rng.choice([8 * rng.integers(1, 160), 128 * rng.integers(1, 10)]))
+        Nl = int(rng.choice([8 * rng.integers(1, 160), 128 * rng.integers(1, 10)]))
+        p = P(M, Kl, Nl)
+        routes |= {axo.axo_fc_route(p, op, *lds)[1] for op, lds in
+                   ((axo.AXO_OP_FWD, (Kl, Nl, Nl)), (axo.AXO_OP_DGRAD, (Nl, Nl, Kl)), (axo.AXO_OP_WGRAD, (Kl, Nl, Nl)))}
+        Xb, Wb, dYb = rand_trio(M, Kl, Nl, 5000 + case)
+        check_trio(p, Xb, Wb, dYb, f"case {case}: {(M, Kl, Nl)}")
+    assert {axo.AXO_ROUTE_TILED, axo.AXO_ROUTE_COVERED, axo.AXO_ROUTE_GENERAL} <= routes
+
+
 def test_empty_dimensions():
     # Kl == 0: forward of an empty sum is zero (then the epilogue); dW is empty
     Xb, Wb, dYb = rand_trio(16, 8, 24, 1)
