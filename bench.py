@@ -41,14 +41,14 @@ PEAK_HBM_GBPS = 8000.0
 # per WRITE_SIZE count.  Keyed by (workload, product); "group" is the single launch of the grouped step.
 FETCH_KIB_PER_COUNT, WRITE_KIB_PER_COUNT = 2.0, 1.0
 MEASURED_TRAFFIC_COUNTS = {
-    ("cfg2", "group"): (304921.3, 90119.7), ("cfg2", "fwd"): (82080.7, 49152.0),
-    ("cfg2", "dgrad"): (98381.9, 16385.4), ("cfg2", "wgrad"): (82010.5, 24586.6),
-    ("cfg3", "group"): (781223.8, 213003.4), ("cfg3", "fwd"): (196811.0, 131097.4),
-    ("cfg3", "dgrad"): (270116.8, 16393.6), ("cfg3", "wgrad"): (196698.5, 65537.3),
-    ("cfg4", "group"): (782209.2, 213013.9), ("cfg4", "fwd"): (267810.6, 16384.4),
-    ("cfg4", "dgrad"): (196709.5, 131100.1), ("cfg4", "wgrad"): (196698.5, 65536.6),
-    ("cfg5", "group"): (1105521.4, 251937.3), ("cfg5", "fwd"): (61680.1, 49152.4),
-    ("cfg5", "dgrad"): (86082.5, 12288.0), ("cfg5", "wgrad"): (83034.5, 18435.7),
+    ("cfg2", "group"): (304881.7, 90117.6), ("cfg2", "fwd"): (82089.3, 49152.0),
+    ("cfg2", "dgrad"): (98376.9, 16385.4), ("cfg2", "wgrad"): (82012.0, 24585.7),
+    ("cfg3", "group"): (782891.4, 213002.6), ("cfg3", "fwd"): (196822.5, 131105.4),
+    ("cfg3", "dgrad"): (269250.1, 16394.7), ("cfg3", "wgrad"): (196700.0, 65536.4),
+    ("cfg4", "group"): (782160.2, 213008.2), ("cfg4", "fwd"): (272950.8, 16386.0),
+    ("cfg4", "dgrad"): (196708.5, 131092.2), ("cfg4", "wgrad"): (196700.0, 65536.2),
+    ("cfg5", "group"): (1087142.1, 251960.1), ("cfg5", "fwd"): (61667.2, 49152.0),
+    ("cfg5", "dgrad"): (86080.5, 12288.0), ("cfg5", "wgrad"): (83036.0, 18440.0),
 }
 MEASURED_TRAFFIC_BYTES = {k: int((f * FETCH_KIB_PER_COUNT + w * WRITE_KIB_PER_COUNT) * 1024)
                           for k, (f, w) in MEASURED_TRAFFIC_COUNTS.items()}
